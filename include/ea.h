@@ -1,0 +1,117 @@
+/*
+ * libea -- Expected-Attention KV-cache compression for AMD MI355X (gfx950), C ABI.
+ *
+ * The library implements the compress step of "Expected Attention" (Sec. 2.2, Eq. 5-9 and
+ * Listing 1 of the paper): per-head statistics of recent queries with the rotary matrix
+ * averaged over the next T positions, the closed-form expected attention of every cached
+ * key, the value-norm-weighted score of every KV pair, top-k selection per KV head and the
+ * gather that compacts K and V.  Every step runs in hand-written HIP kernels.
+ *
+ * Conventions common to all entry points
+ *   - All tensor pointers are DEVICE pointers (16-byte aligned) unless marked host.
+ *     `p` (ea_params) is a HOST pointer and is read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on that stream and return; they never synchronise the host, create
+ *     streams, allocate, free or keep device memory.  Scratch comes through `ws`
+ *     (at least ea_workspace_bytes() bytes, 256-byte aligned, owned by the caller, contents
+ *     undefined between calls).  Calls sharing one `ws` must be ordered on one stream.
+ *   - Errors are return codes; nothing aborts or throws across the ABI.  Argument errors are
+ *     detected on the host before any launch, so outputs are untouched on EA_ERR_INVALID_ARG,
+ *     EA_ERR_UNSUPPORTED and EA_ERR_WORKSPACE.  A failed launch returns EA_ERR_DEVICE.
+ *   - Layouts (row-major, innermost last):
+ *       q_win  [B, Hq,  w,     d]   the w most recent queries, row s at position q_pos0+s
+ *       k, v   [B, Hkv, n_cap, d]   only rows < n are read; head stride is n_cap*d
+ *       mu     [B, Hq,  d]   fp32     sigma [B, Hq, d, d] fp32
+ *       scores [B, Hkv, n]   fp32     idx   [B, Hkv, n_keep] int32, ascending positions
+ *     Query head g belongs to KV head g / (Hq/Hkv).
+ *   - Channel pairing of the rotary embedding: rope_layout 0 pairs (c, c+d/2), 1 pairs
+ *     (2c, 2c+1); pair c turns by position * inv_freq[c].
+ *   - Domain: finite inputs; bf16 keys must satisfy |k| < 4096 (they are narrowed to fp16
+ *     for the matrix cores, and their squares are formed in fp16 after a 2^-4 scaling).
+ */
+#ifndef EA_H
+#define EA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  EA_OK = 0,
+  EA_ERR_INVALID_ARG = 1,  /* null / misaligned pointer, size out of range                    */
+  EA_ERR_UNSUPPORTED = 2,  /* head_dim, dtype, group size or window the kernels do not cover */
+  EA_ERR_WORKSPACE = 3,    /* ws_bytes smaller than ea_workspace_bytes()                      */
+  EA_ERR_DEVICE = 4        /* a kernel launch failed (hipGetLastError)                        */
+} ea_status;
+
+typedef enum { EA_F32 = 0, EA_BF16 = 1 } ea_dtype;
+
+typedef struct {
+  int32_t batch;        /* B  >= 1                                                          */
+  int32_t n_q_heads;    /* Hq, a multiple of n_kv_heads                                     */
+  int32_t n_kv_heads;   /* Hkv >= 1                                                         */
+  int32_t head_dim;     /* d in {64, 128, 256}                                              */
+  int32_t dtype;        /* ea_dtype of q_win, k, v                                          */
+  int32_t rope_layout;  /* 0 half-split pairs (c, c+d/2); 1 interleaved pairs (2c, 2c+1)    */
+  int32_t q_is_rotated; /* 1: q_win holds post-rotary queries (un-rotated inside); 0: pre   */
+  int32_t cov_ddof;     /* covariance divisor is w - cov_ddof; 0 or 1                       */
+  int32_t horizon_T;    /* T of Eq. 6 (paper: 512), >= 1                                    */
+  float epsilon;        /* eps of Eq. 9 (paper: 0.02, or 0), >= 0                           */
+} ea_params;
+
+/* Bytes of scratch any entry point needs for caches of up to n rows per head and a query
+ * window of up to `window` rows.  Returns 0 if the parameters are invalid. */
+size_t ea_workspace_bytes(const ea_params* p, int64_t n, int64_t window);
+
+/* Eq. 5-6: statistics of the position-averaged query distribution.
+ *   u_s = R(q_pos0+s)^T q_s (skipped when q_is_rotated = 0); m, S = mean / covariance of
+ *   the u_s; R-bar = average of R(t_next .. t_next+T-1); mu = R-bar m; sigma = R-bar S R-bar^T.
+ * inv_freq: DEVICE pointer, fp64 [d/2].  Needs 1 + cov_ddof <= window <= 4096. */
+ea_status ea_query_stats(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                         const double* inv_freq, int64_t t_next, float* mu, float* sigma,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 7-9 with ||v|| for ||W_o v|| (Sec. 3.1, implementation details) and the GQA group mean:
+ *   l[g,i] = mu_g.k_i/sqrt(d) + k_i^T sigma_g k_i/(2d);  a[g,.] = softmax_i l[g,.];
+ *   scores[h,i] = (mean_{g in group h} a[g,i] + epsilon) * ||v_i||_2.
+ * Reads k, v rows < n once.  n >= 1. */
+ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
+                   const float* mu, const float* sigma, float* scores,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 2.2 "Compression", Listing 1 top-k: per KV head the n_keep pairs of highest score,
+ * equal scores going to the lower position; idx is written in ascending position order.
+ * Scores must be non-negative and not NaN (compared by bit pattern).  0 <= n_keep <= n. */
+ea_status ea_select(const ea_params* p, const float* scores, int64_t n, int64_t n_keep,
+                    int32_t* idx, void* ws, size_t ws_bytes, void* stream);
+
+/* Listing 1 gather: row idx[j] of every head of k and v moves to row j of k_out / v_out
+ * (same [B, Hkv, n_cap, d] layout).  k_out == k and v_out == v compacts in place; otherwise
+ * the outputs must not overlap the inputs.  idx must be strictly ascending with values < n.
+ * Rows >= n_keep of the outputs are left as they were. */
+ea_status ea_compact(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
+                     const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* Listing 1 end to end on one layer: statistics -> scores -> selection -> in-place compaction
+ * of k and v, all enqueued on `stream` with no host synchronisation in between.
+ * scores_out ([B,Hkv,n]) and idx_out ([B,Hkv,n_keep]) may be NULL. */
+ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                            const double* inv_freq, int64_t t_next, void* k, void* v, int64_t n,
+                            int64_t n_cap, int64_t n_keep, float* scores_out, int32_t* idx_out,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* Listing 1: int(n * (1 - ratio)) in IEEE double, truncated toward zero; -1 if ratio is
+ * outside [0, 1] or n < 0.  Host only. */
+int64_t ea_n_keep(int64_t n, double ratio);
+
+/* Static string for a status code.  Host only. */
+const char* ea_status_string(ea_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EA_H */

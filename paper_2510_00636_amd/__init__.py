@@ -1,0 +1,8 @@
+"""MI355X-native Expected-Attention KV-cache compression: thin Python binding over libea.so.
+
+Every step of the path runs in the HIP kernels of the shared library; this package only
+marshals arguments (pointers, sizes, the stream).  There is no CPU or PyTorch fallback: if the
+library is missing, importing `binding` functions raises."""
+from .binding import (EaError, EaParams, make_params, workspace_bytes, query_stats, score, select,  # noqa: F401
+                      compact, compress_layer, n_keep, status_string, lib_path, load_library,
+                      EA_F32, EA_BF16)

@@ -1,0 +1,136 @@
+"""ctypes binding of include/ea.h -- same names, argument marshalling only.
+
+Tensor arguments are torch CUDA tensors (or anything with .data_ptr()); `stream` is a
+torch.cuda.Stream, a raw hipStream_t integer, or None for torch's current stream."""
+import ctypes
+import os
+
+EA_F32, EA_BF16 = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class EaError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s: %s (status %d)" % (where, status_string(code), code))
+
+
+class EaParams(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("rope_layout", ctypes.c_int32),
+                ("q_is_rotated", ctypes.c_int32), ("cov_ddof", ctypes.c_int32),
+                ("horizon_T", ctypes.c_int32), ("epsilon", ctypes.c_float)]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libea.so")
+
+
+def load_library():
+    """Loads libea.so (built in-tree by paper_2510_00636_amd.build).  Raises if it is absent:
+    there is deliberately no fallback implementation."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError("libea.so not found at %s -- run `python -m paper_2510_00636_amd.build` "
+                           "(or __graft_entry__.build()) first" % path)
+    lib = ctypes.CDLL(path)
+    P, VP, I64, SZ = ctypes.POINTER(EaParams), ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+    lib.ea_workspace_bytes.restype = SZ
+    lib.ea_workspace_bytes.argtypes = [P, I64, I64]
+    lib.ea_query_stats.restype = ctypes.c_int
+    lib.ea_query_stats.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, VP, SZ, VP]
+    lib.ea_score.restype = ctypes.c_int
+    lib.ea_score.argtypes = [P, VP, VP, I64, I64, VP, VP, VP, VP, SZ, VP]
+    lib.ea_select.restype = ctypes.c_int
+    lib.ea_select.argtypes = [P, VP, I64, I64, VP, VP, SZ, VP]
+    lib.ea_compact.restype = ctypes.c_int
+    lib.ea_compact.argtypes = [P, VP, VP, I64, I64, VP, I64, VP, VP, VP, SZ, VP]
+    lib.ea_compress_layer.restype = ctypes.c_int
+    lib.ea_compress_layer.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, VP, VP, SZ, VP]
+    lib.ea_n_keep.restype = I64
+    lib.ea_n_keep.argtypes = [I64, ctypes.c_double]
+    lib.ea_status_string.restype = ctypes.c_char_p
+    lib.ea_status_string.argtypes = [ctypes.c_int]
+    _LIB = lib
+    return lib
+
+
+def make_params(batch, n_q_heads, n_kv_heads, head_dim, dtype, rope_layout=0, q_is_rotated=1,
+                cov_ddof=0, horizon_T=512, epsilon=0.02):
+    return EaParams(batch, n_q_heads, n_kv_heads, head_dim, dtype, rope_layout, q_is_rotated,
+                    cov_ddof, horizon_T, epsilon)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def _stream(s):
+    if s is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(s, int):
+        return ctypes.c_void_p(s)
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(code, where):
+    if code != 0:
+        raise EaError(code, where)
+
+
+def status_string(code):
+    return load_library().ea_status_string(int(code)).decode()
+
+
+def n_keep(n, ratio):
+    return int(load_library().ea_n_keep(int(n), float(ratio)))
+
+
+def workspace_bytes(p, n, window):
+    return int(load_library().ea_workspace_bytes(ctypes.byref(p), int(n), int(window)))
+
+
+def query_stats(p, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, ws, stream=None):
+    _check(load_library().ea_query_stats(ctypes.byref(p), _ptr(q_win), int(window), int(q_pos0),
+                                         _ptr(inv_freq), int(t_next), _ptr(mu), _ptr(sigma),
+                                         _ptr(ws), _nbytes(ws), _stream(stream)), "ea_query_stats")
+
+
+def score(p, k, v, n, n_cap, mu, sigma, scores, ws, stream=None):
+    _check(load_library().ea_score(ctypes.byref(p), _ptr(k), _ptr(v), int(n), int(n_cap), _ptr(mu),
+                                   _ptr(sigma), _ptr(scores), _ptr(ws), _nbytes(ws),
+                                   _stream(stream)), "ea_score")
+
+
+def select(p, scores, n, n_keep_, idx, ws, stream=None):
+    _check(load_library().ea_select(ctypes.byref(p), _ptr(scores), int(n), int(n_keep_), _ptr(idx),
+                                    _ptr(ws), _nbytes(ws), _stream(stream)), "ea_select")
+
+
+def compact(p, k, v, n, n_cap, idx, n_keep_, k_out, v_out, ws, stream=None):
+    _check(load_library().ea_compact(ctypes.byref(p), _ptr(k), _ptr(v), int(n), int(n_cap),
+                                     _ptr(idx), int(n_keep_), _ptr(k_out), _ptr(v_out), _ptr(ws),
+                                     _nbytes(ws), _stream(stream)), "ea_compact")
+
+
+def compress_layer(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep_,
+                   scores_out, idx_out, ws, stream=None):
+    _check(load_library().ea_compress_layer(ctypes.byref(p), _ptr(q_win), int(window), int(q_pos0),
+                                            _ptr(inv_freq), int(t_next), _ptr(k), _ptr(v), int(n),
+                                            int(n_cap), int(n_keep_), _ptr(scores_out),
+                                            _ptr(idx_out), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "ea_compress_layer")

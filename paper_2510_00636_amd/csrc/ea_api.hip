@@ -1,0 +1,190 @@
+// extern "C" entry points of libea: host-side validation, then the launch sequence on the
+// caller's stream.  No allocation, no synchronisation, no state besides a cached CU count.
+#include <hip/hip_runtime.h>
+
+#include "ea_kernels.h"
+
+namespace ea {
+
+int device_num_cu() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+static inline bool aligned16(const void* p) { return p && ((uintptr_t)p & 15u) == 0; }
+static inline bool aligned256(const void* p) { return p && ((uintptr_t)p & 255u) == 0; }
+#define EA_TRY(expr)                                   \
+  do {                                                 \
+    if ((expr) != hipSuccess) return EA_ERR_DEVICE;    \
+  } while (0)
+
+static ea_status check_ws(const Dims& d, int64_t n, int64_t window, void* ws, size_t ws_bytes,
+                          WsLayout* L) {
+  if (!aligned256(ws)) return EA_ERR_INVALID_ARG;
+  *L = make_ws_layout(d, n, window);
+  if (ws_bytes < L->total) return EA_ERR_WORKSPACE;
+  return EA_OK;
+}
+
+static ea_status run_stats(const Dims& d, const void* q_win, int64_t window, int64_t q_pos0,
+                           const double* inv_freq, int64_t t_next, float* mu, float* sigma,
+                           char* ws, const WsLayout& L, hipStream_t st) {
+  float2* tab = (float2*)(ws + L.tab);
+  EA_TRY(launch_rope_table(d, inv_freq, q_pos0, t_next, (int)window, tab, st));
+  EA_TRY(launch_stats(d, q_win, (int)window, tab, mu, sigma, st));
+  return EA_OK;
+}
+
+// hist0 != nullptr: the finalize pass also fills the first radix-select histogram
+static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
+                           const float* mu, const float* sigma, float* scores, uint32_t* hist0,
+                           char* ws, const WsLayout& L, hipStream_t st) {
+  float* vnorm = (float*)(ws + L.vnorm);
+  if (d.dtype == EA_BF16) {
+    ScorePlan sp = make_score_plan(d, n, device_num_cu());
+    uint4* frags = (uint4*)(ws + L.frags);
+    float* post = (float*)(ws + L.post);
+    EA_TRY(launch_prep_frags(d, sp, mu, sigma, frags, post, st));
+    EA_TRY(launch_score_mfma(d, sp, k, v, n, n_cap, frags, post, (float*)(ws + L.logits), vnorm,
+                             (float2*)(ws + L.part), st));
+    EA_TRY(launch_finalize(d, n, ws + L.logits, 0, vnorm, ws + L.part, sp.nchunk, scores, hist0, st));
+  } else {
+    int nchunk = 0;
+    EA_TRY(launch_score_f32(d, k, v, n, n_cap, mu, sigma, (double*)(ws + L.logits), vnorm,
+                            (double2*)(ws + L.part), &nchunk, st));
+    EA_TRY(launch_finalize(d, n, ws + L.logits, 1, vnorm, ws + L.part, nchunk, scores, hist0, st));
+  }
+  return EA_OK;
+}
+
+static size_t hist_words(const Dims& d) { return (size_t)d.units() * 3 * kSelBins; }
+static size_t flag_words(const Dims& d, int64_t n_keep) {
+  return 2 * (size_t)d.units() * ((n_keep + kCompactRows - 1) / kCompactRows) + 1;
+}
+
+}  // namespace ea
+
+using namespace ea;
+
+extern "C" {
+
+ea_status ea_query_stats(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                         const double* inv_freq, int64_t t_next, float* mu, float* sigma, void* ws,
+                         size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(q_win) || !aligned16(mu) || !aligned16(sigma) || !inv_freq ||
+      ((uintptr_t)inv_freq & 7u))
+    return EA_ERR_INVALID_ARG;
+  if (window < 1 + d.ddof || q_pos0 < 0 || t_next < 0) return EA_ERR_INVALID_ARG;
+  if (window > kMaxWindow) return EA_ERR_UNSUPPORTED;
+  WsLayout L;
+  if ((s = check_ws(d, 1, window, ws, ws_bytes, &L)) != EA_OK) return s;
+  return run_stats(d, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, (char*)ws, L,
+                   (hipStream_t)stream);
+}
+
+ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
+                   const float* mu, const float* sigma, float* scores, void* ws, size_t ws_bytes,
+                   void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(mu) || !aligned16(sigma) || !aligned16(scores))
+    return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > ((int64_t)1 << 30)) return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  return run_score(d, k, v, n, n_cap, mu, sigma, scores, nullptr, (char*)ws, L, (hipStream_t)stream);
+}
+
+ea_status ea_select(const ea_params* p, const float* scores, int64_t n, int64_t n_keep, int32_t* idx,
+                    void* ws, size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (n < 1 || n > ((int64_t)1 << 30) || n_keep < 0 || n_keep > n) return EA_ERR_INVALID_ARG;
+  if (!aligned16(scores) || (n_keep > 0 && !aligned16(idx))) return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  if (n_keep == 0) return EA_OK;
+  hipStream_t st = (hipStream_t)stream;
+  uint32_t* hist = (uint32_t*)((char*)ws + L.hist);
+  EA_TRY(launch_zero(hist, hist_words(d), st));
+  EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, (uint32_t*)((char*)ws + L.blk), false, st));
+  return EA_OK;
+}
+
+ea_status ea_compact(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
+                     const int32_t* idx, int64_t n_keep, void* k_out, void* v_out, void* ws,
+                     size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+    return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > ((int64_t)1 << 30) || n_keep < 0 || n_keep > n)
+    return EA_ERR_INVALID_ARG;
+  if ((k_out == k) != (v_out == v)) return EA_ERR_INVALID_ARG;   // both in place or neither
+  if (k_out == v || v_out == k || (k_out == v_out)) return EA_ERR_INVALID_ARG;
+  if (n_keep > 0 && !aligned16(idx)) return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  if (n_keep == 0) return EA_OK;
+  hipStream_t st = (hipStream_t)stream;
+  uint32_t* flags = (uint32_t*)((char*)ws + L.flags);
+  if (k_out == k) EA_TRY(launch_zero(flags, flag_words(d, n_keep), st));
+  EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k_out, v_out, flags, st));
+  return EA_OK;
+}
+
+ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                            const double* inv_freq, int64_t t_next, void* k, void* v, int64_t n,
+                            int64_t n_cap, int64_t n_keep, float* scores_out, int32_t* idx_out,
+                            void* ws, size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || k == v || !inv_freq ||
+      ((uintptr_t)inv_freq & 7u))
+    return EA_ERR_INVALID_ARG;
+  if ((scores_out && !aligned16(scores_out)) || (idx_out && !aligned16(idx_out)))
+    return EA_ERR_INVALID_ARG;
+  if (window < 1 + d.ddof || q_pos0 < 0 || t_next < 0) return EA_ERR_INVALID_ARG;
+  if (window > kMaxWindow) return EA_ERR_UNSUPPORTED;
+  if (n < 1 || n > n_cap || n > ((int64_t)1 << 30) || n_keep < 0 || n_keep > n)
+    return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, window, ws, ws_bytes, &L)) != EA_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  char* w = (char*)ws;
+  float* mu = (float*)(w + L.mu);
+  float* sigma = (float*)(w + L.sigma);
+  float* scores = scores_out ? scores_out : (float*)(w + L.scores);
+  int32_t* idx = idx_out ? idx_out : (int32_t*)(w + L.idx);
+  uint32_t* hist = (uint32_t*)(w + L.hist);
+  uint32_t* flags = (uint32_t*)(w + L.flags);
+  // hist .. flags are adjacent regions of ws: one clearing launch covers histograms, block
+  // counts and the compaction flags
+  const size_t clear_words = (L.flags - L.hist) / 4 + flag_words(d, n_keep);
+  EA_TRY(launch_zero(hist, clear_words, st));
+  if ((s = run_stats(d, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, w, L, st)) != EA_OK)
+    return s;
+  if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores, n_keep > 0 ? hist : nullptr, w, L, st)) != EA_OK)
+    return s;
+  if (n_keep == 0) return EA_OK;
+  EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, (uint32_t*)(w + L.blk), true, st));
+  EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k, v, flags, st));
+  return EA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,41 @@
+// Launch wrappers of the HIP kernels (one translation unit per stage).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "ea_common.h"
+
+namespace ea {
+
+// ea_stats.hip
+hipError_t launch_rope_table(const Dims& d, const double* inv_freq, int64_t q_pos0, int64_t t_next,
+                             int w, float2* tab, hipStream_t st);
+hipError_t launch_stats(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
+                        float* sigma, hipStream_t st);
+hipError_t launch_prep_frags(const Dims& d, const ScorePlan& sp, const float* mu,
+                             const float* sigma, uint4* frags, float* post, hipStream_t st);
+
+// ea_score.hip
+hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
+                             int64_t n, int64_t n_cap, const uint4* frags, const float* post,
+                             float* logits, float* vnorm, float2* part, hipStream_t st);
+hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
+                            const float* mu, const float* sigma, double* logits, float* vnorm,
+                            double2* part, int* nchunk_out, hipStream_t st);
+// scores = (mean_g exp(l_g - lse_g) + eps) * vnorm; hist0 (nullable): first radix digit
+hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
+                           const float* vnorm, const void* part, int nchunk, float* scores,
+                           uint32_t* hist0, hipStream_t st);
+
+// ea_select.hip
+hipError_t launch_select(const Dims& d, const float* scores, int64_t n, int64_t n_keep, int32_t* idx,
+                         uint32_t* hist, uint32_t* blk, bool hist0_done, hipStream_t st);
+hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st);
+
+// ea_compact.hip
+hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
+                          const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
+                          uint32_t* flags, hipStream_t st);
+
+int device_num_cu();
+
+}  // namespace ea

@@ -1,0 +1,522 @@
+// Scoring kernels: Eq. 7 (expected unnormalised attention, as a logit), Eq. 8 (softmax over
+// all cached keys) and Eq. 9 with ||v|| and the GQA group mean.
+//
+//   pass A  k_score_mfma / k_score_f32 : stream K and V once; per key the G logits
+//           l_g = mu_g.k/sqrt(d) + k^T Sigma_g k/(2d) and ||v||; per workgroup an online
+//           (max, sum exp) pair per query head.
+//   pass B  k_finalize : combine the pairs into log-sum-exp per head, then
+//           score = (mean_g exp(l_g - lse_g) + eps) * ||v||.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "ea_kernels.h"
+
+namespace ea {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+// native 16-byte vector: plain loads/stores the optimiser can keep in registers (HIP's uint4 is
+// a struct whose copies go through memcpy)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct ScoreArgs {
+  const u32x4* k;
+  const u32x4* v;
+  long long n, n_cap;
+  const u32x4* frags;
+  const float* post;
+  float* logits;
+  float* vnorm;
+  float2* part;
+  int G, passes, span, nchunk, units, nfrag;
+};
+
+__device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
+  // bf16 -> fp32 is a 16-bit shift; fp32 -> fp16 is exact for |x| in [2^-14, 65504]
+  // (a bf16 significand has 8 bits, fp16 keeps 11), so round-toward-zero loses nothing there.
+  auto cv = [](uint32_t w) {
+    return __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
+  };
+  auto a = cv(r.x), b = cv(r.y), c = cv(r.z), d = cv(r.w);
+  half8 o;
+  o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
+  o[4] = c[0]; o[5] = c[1]; o[6] = d[0]; o[7] = d[1];
+  return o;
+}
+
+__device__ __forceinline__ float sumsq_bf16x8(u32x4 r) {
+  float s = 0.f;
+  bf16x2 a = __builtin_bit_cast(bf16x2, r.x), b = __builtin_bit_cast(bf16x2, r.y);
+  bf16x2 c = __builtin_bit_cast(bf16x2, r.z), d = __builtin_bit_cast(bf16x2, r.w);
+  s = __builtin_amdgcn_fdot2_f32_bf16(a, a, s, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(b, b, s, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(c, c, s, false);
+  s = __builtin_amdgcn_fdot2_f32_bf16(d, d, s, false);
+  return s;
+}
+
+// merge two online-softmax states (m, s): value = s * exp(m)
+__device__ __forceinline__ void merge_ms(float& m, float& s, float m2, float s2) {
+  float mn = fmaxf(m, m2);
+  if (mn == -INFINITY) { s = 0.f; m = mn; return; }
+  s = s * __expf(m - mn) + s2 * __expf(m2 - mn);
+  m = mn;
+}
+
+// compile-time loop: f(std::integral_constant<int, 0>) ... f(<N-1>), so that every register
+// array index below is a constant
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
+// accumulator row rho of a 32x32 tile lives in register ROW_V(rho) of the lanes with
+// lane / 32 == ROW_HH(rho)  (column = lane % 32)
+#define ROW_V(rho) (4 * ((rho) / 8) + (rho) % 4)
+#define ROW_HH(rho) (((rho) / 4) % 2)
+
+// ---------------------------------------------------------------------------------------
+// One wavefront scores 32 keys per iteration.  Lane l = (r = l % 32, hh = l / 32) owns the
+// channels hh*d/2 .. hh*d/2 + d/2 - 1 of key r as fp16 (B operand of the 32x32x16 MFMA), the
+// fragments of M (A operand) come from LDS, and the accumulator layout hands the lane the
+// same channels back, so  sum_j acc_j k_j  is 16 mixed-precision FMAs per output tile.
+// K rows reach that layout through a per-wave LDS staging buffer (coalesced 16-byte global
+// loads in, conflict-free 16-byte LDS reads out); V rows are squared and summed straight
+// from the coalesced layout.  The next tile's K and V loads are issued before the matrix
+// work of the current one.
+template <int D, int GH, int NW>
+__global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
+  constexpr int NKS = D / 16, NJT = D / 32, NF = NJT * (NJT + 1);
+  constexpr int NFRAG = GH * NF + 2 * NKS;
+  constexpr int CPR = D / 8;            // 16-byte chunks per row
+  constexpr int RPL = 64 / CPR;         // rows per wave-wide load
+  constexpr int NL = 32 / RPL;          // wave-wide loads per 32-key tile
+  constexpr int NKH = NKS / 2;          // k-steps staged per phase
+  constexpr int RP = CPR / 2;           // staged chunks per row and phase
+  constexpr int RPS = 16 / RP;          // staged rows per 256 bytes (one sweep of the LDS banks)
+  extern __shared__ u32x4 smem[];
+  const half8* fr = reinterpret_cast<const half8*>(smem);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  u32x4* stg = smem + NFRAG * 64 + wave * (16 * CPR);
+  float2* red = reinterpret_cast<float2*>(smem + NFRAG * 64 + NW * (16 * CPR));
+
+  const int bid = blockIdx.x;
+  const int unit = bid % a.units;
+  const int t2 = bid / a.units;
+  const int chunk = t2 % a.nchunk, pass = t2 / a.nchunk;
+  const int g0 = pass * GH;
+  const bool do_v = pass == 0;
+
+  {  // fragments of this (unit, pass) -> LDS
+    const u32x4* src = a.frags + ((size_t)unit * a.passes + pass) * NFRAG * 64;
+    for (int i = tid; i < NFRAG * 64; i += NW * 64) smem[i] = src[i];
+  }
+  float pq[GH], pm[GH];
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+    const bool ok = g0 + g < a.G;
+    pq[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 0] : 0.f;
+    pm[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 1] : 0.f;
+  }
+  __syncthreads();
+
+  const int r = lane & 31, hh = lane >> 5;
+  const int lrow = lane / CPR, lch = lane % CPR;
+  const long long key_lo = (long long)chunk * a.span;
+  const long long key_hi = min(key_lo + (long long)a.span, a.n);
+  const u32x4* kbase = a.k + (size_t)unit * a.n_cap * CPR;
+  const u32x4* vbase = a.v + (size_t)unit * a.n_cap * CPR;
+
+  float m_run[GH], s_run[GH];
+#pragma unroll
+  for (int g = 0; g < GH; ++g) { m_run[g] = -INFINITY; s_run[g] = 0.f; }
+
+  u32x4 kraw[NL], vraw[NL];
+  long long key0 = key_lo + (long long)wave * 32;
+  // rows are clamped to n-1, so these loads are always in bounds (also for an idle wave)
+#pragma unroll
+  for (int j = 0; j < NL; ++j) {
+    const long long row = min(key0 + j * RPL + lrow, a.n - 1);
+    kraw[j] = kbase[row * CPR + lch];
+    vraw[j] = do_v ? vbase[row * CPR + lch] : u32x4{0u, 0u, 0u, 0u};
+  }
+
+  for (; key0 < key_hi; key0 += NW * 32) {
+    // ---- K: coalesced registers -> LDS -> MFMA B layout.  Two phases, each staging one half
+    //      of every lane's k-steps for all 32 rows (half-size buffer, all lanes busy).
+    half8 Kh[NKS];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      if (((lch % NKS) / NKH) == hf) {
+        const int sc = (lch / NKS) * NKH + (lch % NKH);
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+          const int rho = j * RPL + lrow;
+          stg[rho * RP + (sc ^ ((rho / RPS) & (RP - 1)))] = kraw[j];
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int q = 0; q < NKH; ++q) {
+        const int sc = hh * NKH + q;
+        Kh[hf * NKH + q] = bf16x8_to_half8(stg[r * RP + (sc ^ ((r / RPS) & (RP - 1)))]);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+    // ---- V: squared norms from the coalesced layout
+    if (do_v) {
+#pragma unroll
+      for (int j = 0; j < NL; ++j) {
+        float ss = sumsq_bf16x8(vraw[j]);
+#pragma unroll
+        for (int o = CPR / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+        const long long row = key0 + j * RPL + lrow;
+        if (lch == 0 && row < a.n) a.vnorm[(size_t)unit * a.n + row] = sqrtf(ss);
+      }
+    }
+    // ---- prefetch the next tile
+    const long long nkey0 = key0 + NW * 32;
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {   // past the span this re-reads a clamped row; harmless
+      const long long row = min(nkey0 + j * RPL + lrow, a.n - 1);
+      kraw[j] = kbase[row * CPR + lch];
+      vraw[j] = do_v ? vbase[row * CPR + lch] : u32x4{0u, 0u, 0u, 0u};
+    }
+    // ---- extra tile: rows g = mu head, GH+g = mu tail (times k); 2GH+g = diagonal residual of
+    //      M (times k^2/256).  Folded into per-head logit terms so the tile dies early.
+    float lin[GH];
+    {
+      floatx16 ex = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      static_for<NKS>([&](auto kt_) {
+        constexpr int kt = decltype(kt_)::value;
+        ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[(GH * NF + kt) * 64 + lane], Kh[kt], ex, 0, 0, 0);
+      });
+      static_for<NKS>([&](auto kt_) {
+        constexpr int kt = decltype(kt_)::value;
+        half8 t = Kh[kt] * (_Float16)0.0625f;
+        t = t * t;
+        ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[(GH * NF + NKS + kt) * 64 + lane], t, ex, 0, 0, 0);
+      });
+      static_for<GH>([&](auto g_) {
+        constexpr int g = decltype(g_)::value;
+        float e = 0.f;
+        if (hh == ROW_HH(g)) e += ex[ROW_V(g)] * pm[g];
+        if (hh == ROW_HH(GH + g)) e += ex[ROW_V(GH + g)] * pm[g];
+        if (hh == ROW_HH(2 * GH + g)) e += ex[ROW_V(2 * GH + g)] * (256.0f * pq[g]);
+        lin[g] = e;
+      });
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- quadratic forms on the matrix cores
+    float partial[GH];
+    static_for<GH>([&](auto g_) {
+      constexpr int g = decltype(g_)::value;
+      partial[g] = 0.f;
+      static_for<NJT>([&](auto jt_) {
+        constexpr int jt = decltype(jt_)::value;
+        floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        constexpr int fbase = g * NF + jt * (jt + 1);
+        static_for<2 * jt + 2>([&](auto kt_) {
+          constexpr int kt = decltype(kt_)::value;
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[(fbase + kt) * 64 + lane], Kh[kt], acc, 0, 0, 0);
+        });
+        static_for<16>([&](auto v_) {
+          constexpr int v = decltype(v_)::value;
+          constexpr int x = jt * 16 + v;
+          partial[g] = fmaf(acc[v], (float)Kh[x / 8][x % 8], partial[g]);
+        });
+        // pin the dot product here: otherwise the optimiser sinks it past the following tiles
+        // and keeps every accumulator tile alive
+        asm volatile("" : "+v"(partial[g]));
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
+    const bool valid = key0 + r < a.n;
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      float lg = partial[g] * pq[g] + lin[g];
+      lg += __shfl_xor(lg, 32);
+      if (valid && g0 + g < a.G) {
+        if (hh == 0) a.logits[((size_t)unit * a.G + g0 + g) * a.n + key0 + r] = lg;
+        float mn = fmaxf(m_run[g], lg);
+        s_run[g] = s_run[g] * __expf(m_run[g] - mn) + __expf(lg - mn);
+        m_run[g] = mn;
+      }
+    }
+  }
+
+  // ---- (max, sum) of this workgroup's keys, per head
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+    float m = m_run[g], s = s_run[g];
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) {
+      float m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
+      merge_ms(m, s, m2, s2);
+    }
+    if (lane == 0) red[wave * GH + g] = make_float2(m, s);
+  }
+  __syncthreads();
+  if (tid < GH && g0 + tid < a.G) {
+    float m = -INFINITY, s = 0.f;
+    for (int w = 0; w < NW; ++w) {
+      float2 o = red[w * GH + tid];
+      merge_ms(m, s, o.x, o.y);
+    }
+    a.part[((size_t)unit * a.G + g0 + tid) * a.nchunk + chunk] = make_float2(m, s);
+  }
+}
+
+template <int D, int GH, int NW>
+static hipError_t launch_one(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st) {
+  auto kern = k_score_mfma<D, GH, NW>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp.lds_bytes);
+  if (e != hipSuccess) return e;
+  int grid = a.units * a.nchunk * a.passes;
+  kern<<<grid, NW * 64, sp.lds_bytes, st>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
+                             int64_t n, int64_t n_cap, const uint4* frags, const float* post,
+                             float* logits, float* vnorm, float2* part, hipStream_t st) {
+  ScoreArgs a;
+  a.k = (const u32x4*)k;
+  a.v = (const u32x4*)v;
+  a.n = n;
+  a.n_cap = n_cap;
+  a.frags = (const u32x4*)frags;
+  a.post = post;
+  a.logits = logits;
+  a.vnorm = vnorm;
+  a.part = part;
+  a.G = d.G;
+  a.passes = sp.passes;
+  a.span = sp.span;
+  a.nchunk = sp.nchunk;
+  a.units = d.units();
+  a.nfrag = sp.nfrag;
+#define EA_CASE(DD, GG, WW) \
+  if (d.D == DD && sp.GH == GG && sp.NW == WW) return launch_one<DD, GG, WW>(a, sp, st)
+  EA_CASE(64, 1, 8);
+  EA_CASE(64, 2, 8);
+  EA_CASE(64, 4, 8);
+  EA_CASE(64, 8, 8);
+  EA_CASE(128, 1, 8);
+  EA_CASE(128, 2, 8);
+  EA_CASE(128, 3, 8);
+  EA_CASE(128, 4, 8);
+  EA_CASE(128, 5, 8);
+  EA_CASE(256, 1, 4);
+#undef EA_CASE
+  return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 caches: everything in fp64 on the vector units (the 1e-5 score tolerance of this
+// path leaves no room for fp32 accumulation of a d^2-term quadratic form).  One workgroup
+// = (unit, query head, span of keys); 64 keys at a time, K tile in LDS, thread (key, quarter
+// of the output channels).
+template <int D>
+__global__ __launch_bounds__(256) void k_score_f32(const float* __restrict__ k,
+                                                   const float* __restrict__ v, long long n,
+                                                   long long n_cap, const float* __restrict__ mu,
+                                                   const float* __restrict__ sigma, int G, int units,
+                                                   int span, int nchunk, double* __restrict__ logits,
+                                                   float* __restrict__ vnorm,
+                                                   double2* __restrict__ part) {
+  constexpr int QW = D / 4;
+  extern __shared__ float s_k[];            // [64][D + 1]
+  __shared__ double s_red[4][64];
+  __shared__ double s_ms[2];
+  const int tid = threadIdx.x, r = tid & 63, qd = tid >> 6;
+  const int unit = blockIdx.x % units;
+  const int t2 = blockIdx.x / units;
+  const int gq = t2 % G, chunk = t2 / G;
+  const float* S = sigma + ((size_t)unit * G + gq) * D * D;
+  const float* M = mu + ((size_t)unit * G + gq) * D;
+  const float* kb = k + (size_t)unit * n_cap * D;
+  const float* vb = v + (size_t)unit * n_cap * D;
+  const long long key_lo = (long long)chunk * span, key_hi = min(key_lo + (long long)span, n);
+  double m_run = -INFINITY, s_run = 0.0;   // thread r < 64 of quarter 0 tracks key slot r
+  for (long long key0 = key_lo; key0 < key_hi; key0 += 64) {
+    __syncthreads();
+    for (int e = tid; e < 64 * D; e += 256) {
+      int rr = e / D, c = e - rr * D;
+      long long row = min(key0 + rr, n - 1);
+      s_k[rr * (D + 1) + c] = kb[row * D + c];
+    }
+    __syncthreads();
+    double y[QW];
+#pragma unroll
+    for (int j = 0; j < QW; ++j) y[j] = 0.0;
+    for (int c = 0; c < D; ++c) {
+      const double kc = (double)s_k[r * (D + 1) + c];
+      const float* Sr = S + (size_t)c * D + qd * QW;
+#pragma unroll
+      for (int j = 0; j < QW; ++j) y[j] = fma(kc, (double)Sr[j], y[j]);
+    }
+    double quad = 0.0, lin = 0.0;
+#pragma unroll
+    for (int j = 0; j < QW; ++j) {
+      const double kj = (double)s_k[r * (D + 1) + qd * QW + j];
+      quad = fma(y[j], kj, quad);
+      lin = fma((double)M[qd * QW + j], kj, lin);
+    }
+    s_red[qd][r] = lin / sqrt((double)D) + quad / (2.0 * D);
+    __syncthreads();
+    if (qd == 0 && key0 + r < n) {
+      double lg = s_red[0][r] + s_red[1][r] + s_red[2][r] + s_red[3][r];
+      logits[((size_t)unit * G + gq) * n + key0 + r] = lg;
+      double mn = fmax(m_run, lg);
+      s_run = s_run * exp(m_run - mn) + exp(lg - mn);
+      m_run = mn;
+    }
+    if (gq == 0) {   // value norms, once per unit
+      __syncthreads();
+      long long row = min(key0 + r, n - 1);
+      double ss = 0.0;
+      for (int j = 0; j < QW; ++j) {
+        double x = (double)vb[row * D + qd * QW + j];
+        ss = fma(x, x, ss);
+      }
+      s_red[qd][r] = ss;
+      __syncthreads();
+      if (qd == 0 && key0 + r < n)
+        vnorm[(size_t)unit * n + key0 + r] =
+            (float)sqrt(s_red[0][r] + s_red[1][r] + s_red[2][r] + s_red[3][r]);
+    }
+  }
+  // reduce the 64 key slots
+  __syncthreads();
+  if (qd == 0) {
+    double m = m_run, s = s_run;
+    for (int o = 32; o >= 1; o >>= 1) {
+      double m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
+      double mn = fmax(m, m2);
+      if (mn == -INFINITY) { s = 0.0; m = mn; }
+      else { s = s * exp(m - mn) + s2 * exp(m2 - mn); m = mn; }
+    }
+    if (r == 0) part[((size_t)unit * G + gq) * nchunk + chunk] = make_double2(m, s);
+  }
+  (void)s_ms;
+}
+
+hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
+                            const float* mu, const float* sigma, double* logits, float* vnorm,
+                            double2* part, int* nchunk_out, hipStream_t st) {
+  int64_t span = (n + 1023) / 1024;
+  span = (span + 63) / 64 * 64;
+  if (span < 64) span = 64;
+  int nchunk = (int)((n + span - 1) / span);
+  *nchunk_out = nchunk;
+  int grid = d.units() * d.G * nchunk;
+  size_t lds = (size_t)64 * (d.D + 1) * sizeof(float);
+#define EA_F32(DD)                                                                              \
+  if (d.D == DD) {                                                                              \
+    auto kern = k_score_f32<DD>;                                                                \
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                     \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   \
+    if (e != hipSuccess) return e;                                                              \
+    kern<<<grid, 256, lds, st>>>((const float*)k, (const float*)v, n, n_cap, mu, sigma, d.G,    \
+                                 d.units(), (int)span, nchunk, logits, vnorm, part);            \
+    return hipGetLastError();                                                                   \
+  }
+  EA_F32(64)
+  EA_F32(128)
+  EA_F32(256)
+#undef EA_F32
+  return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------------
+// Pass B.  One workgroup = 1024 keys of one unit.  LT is the logit type (float: bf16 caches,
+// double: fp32 caches).  With hist0 != nullptr the first radix-select digit (top 11 bits of
+// the score's bit pattern) is histogrammed on the way out.
+template <typename LT>
+struct LT2;
+template <>
+struct LT2<float> { typedef float2 type; };
+template <>
+struct LT2<double> { typedef double2 type; };
+
+__device__ __forceinline__ float ea_exp(float x) { return expf(x); }
+__device__ __forceinline__ double ea_exp(double x) { return exp(x); }
+__device__ __forceinline__ float ea_log(float x) { return logf(x); }
+__device__ __forceinline__ double ea_log(double x) { return log(x); }
+
+template <typename LT>
+__global__ __launch_bounds__(256) void k_finalize(const LT* __restrict__ logits,
+                                                  const float* __restrict__ vnorm,
+                                                  const typename LT2<LT>::type* __restrict__ part,
+                                                  int G, int nchunk, long long n, float eps,
+                                                  float* __restrict__ scores,
+                                                  uint32_t* __restrict__ hist0) {
+  __shared__ LT s_lse[64];
+  __shared__ uint32_t s_hist[kSelBins];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int unit = blockIdx.x;
+  if (hist0)
+    for (int i = tid; i < kSelBins; i += 256) s_hist[i] = 0;
+  for (int g = wave; g < G; g += 4) {
+    const typename LT2<LT>::type* p = part + ((size_t)unit * G + g) * nchunk;
+    LT m = -INFINITY, s = 0;
+    for (int c = lane; c < nchunk; c += 64) {
+      LT m2 = p[c].x, s2 = p[c].y;
+      LT mn = m > m2 ? m : m2;
+      if (mn == -INFINITY) { s = 0; m = mn; }
+      else { s = s * ea_exp(m - mn) + s2 * ea_exp(m2 - mn); m = mn; }
+    }
+    for (int o = 32; o >= 1; o >>= 1) {
+      LT m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
+      LT mn = m > m2 ? m : m2;
+      if (mn == -INFINITY) { s = 0; m = mn; }
+      else { s = s * ea_exp(m - mn) + s2 * ea_exp(m2 - mn); m = mn; }
+    }
+    if (lane == 0) s_lse[g] = m + ea_log(s);
+  }
+  __syncthreads();
+  const long long base = (long long)blockIdx.y * 1024;
+  const LT invG = (LT)1 / (LT)G;
+  for (int it = 0; it < 4; ++it) {
+    const long long i = base + it * 256 + tid;
+    if (i < n) {
+      LT acc = 0;
+      for (int g = 0; g < G; ++g) acc += ea_exp(logits[((size_t)unit * G + g) * n + i] - s_lse[g]);
+      float sc = (float)((acc * invG + (LT)eps) * (LT)vnorm[(size_t)unit * n + i]);
+      scores[(size_t)unit * n + i] = sc;
+      if (hist0) atomicAdd(&s_hist[__float_as_uint(sc) >> 21], 1u);
+    }
+  }
+  if (hist0) {
+    __syncthreads();
+    for (int i = tid; i < kSelBins; i += 256) {
+      uint32_t c = s_hist[i];
+      if (c) atomicAdd(&hist0[(size_t)unit * 3 * kSelBins + i], c);
+    }
+  }
+}
+
+hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
+                           const float* vnorm, const void* part, int nchunk, float* scores,
+                           uint32_t* hist0, hipStream_t st) {
+  dim3 grid(d.units(), (unsigned)((n + 1023) / 1024));
+  if (logits_f64)
+    k_finalize<double><<<grid, 256, 0, st>>>((const double*)logits, vnorm, (const double2*)part, d.G,
+                                             nchunk, n, d.eps, scores, hist0);
+  else
+    k_finalize<float><<<grid, 256, 0, st>>>((const float*)logits, vnorm, (const float2*)part, d.G,
+                                            nchunk, n, d.eps, scores, hist0);
+  return hipGetLastError();
+}
+
+}  // namespace ea

@@ -1,0 +1,245 @@
+"""GPU parity: every C-ABI entry point against the fp64 oracle on the same seeded inputs.
+
+Tolerances (from the benchmark spec): scores within 2e-3 relative for bf16 caches (fp32
+accumulation), 1e-5 for fp32 caches; kept-index sets equal to the oracle's except where oracle
+scores lie within that tolerance of the threshold, and bit-exact top-k of the kernel's own
+scores; compacted bytes bit-exact given the indices."""
+import numpy as np
+import pytest
+
+from ea_inputs import CONFIGS, make_layer, widen
+from oracle import ea_oracle as O
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-3, "f32": 1e-5}
+MINI = {
+    "c1": (CONFIGS["c1"], dict()),                                            # the tiny fp32 config as it is
+    "c2mini": (CONFIGS["c2"], dict(n=3000, window=128)),                      # ragged tail, several tiles
+    "c4mini": (CONFIGS["c4"].with_(batch=2), dict(n=1500, window=128)),       # d=256, G=2, batch 2
+    "c5mini": (CONFIGS["c5"], dict(n=1100, window=512, pos0=30000)),          # G=5, window 512, offset positions
+    "d64bf16": (CONFIGS["c2"].with_(head_dim=64, n_q_heads=16, n_kv_heads=2), dict(n=700, window=40)),  # G=8
+}
+
+
+def _oracle_stats(cfg, lay, **kw):
+    return O.query_stats(widen(lay["q_win"]), lay["q_pos0"], lay["inv_freq"], lay["t_next"],
+                         T=cfg.horizon_T, **kw)
+
+
+# ------------------------------------------------------------------------- ea_query_stats
+@pytest.mark.parametrize("name", list(MINI))
+def test_query_stats(name):
+    cfg, kw = MINI[name]
+    lay = make_layer(cfg, **kw)
+    mu, sg = P.run_query_stats(cfg, lay)
+    rmu, rsg = _oracle_stats(cfg, lay)
+    P.check_stats(mu, sg, rmu, rsg)
+
+
+@pytest.mark.parametrize("variant", ["interleaved", "ddof1", "pre_rope", "T1", "w1"])
+def test_query_stats_variants(variant):
+    cfg = CONFIGS["c2"].with_(n_q_heads=4, n_kv_heads=2)
+    if variant == "interleaved":
+        lay = make_layer(cfg, n=500, window=48, interleaved=True)
+        mu, sg = P.run_query_stats(cfg, lay, rope_layout=1)
+        rmu, rsg = _oracle_stats(cfg, lay, layout=O.INTERLEAVED)
+    elif variant == "ddof1":
+        lay = make_layer(cfg, n=500, window=48)
+        mu, sg = P.run_query_stats(cfg, lay, ddof=1)
+        rmu, rsg = _oracle_stats(cfg, lay, ddof=1)
+    elif variant == "pre_rope":
+        lay = make_layer(cfg, n=500, window=48, pre_rope_queries=True)
+        mu, sg = P.run_query_stats(cfg, lay, q_is_rotated=0)
+        rmu, rsg = _oracle_stats(cfg, lay, q_is_rotated=False)
+    elif variant == "T1":
+        lay = make_layer(cfg, n=500, window=48)
+        mu, sg = P.run_query_stats(cfg, lay, T=1)
+        rmu, rsg = O.query_stats(widen(lay["q_win"]), lay["q_pos0"], lay["inv_freq"], lay["t_next"], T=1)
+    else:   # a single query: zero covariance
+        lay = make_layer(cfg, n=500, window=1)
+        mu, sg = P.run_query_stats(cfg, lay)
+        rmu, rsg = _oracle_stats(cfg, lay)
+        assert np.all(sg == 0)
+    P.check_stats(mu, sg, rmu, rsg)
+
+
+# ------------------------------------------------------------------------------- ea_score
+@pytest.mark.parametrize("eps", [0.02, 0.0])
+@pytest.mark.parametrize("name", list(MINI))
+def test_score(name, eps):
+    cfg, kw = MINI[name]
+    lay = make_layer(cfg, **kw)
+    rmu, rsg = _oracle_stats(cfg, lay)
+    mu32, sg32 = rmu.astype(np.float32), rsg.astype(np.float32)    # the call's inputs are fp32
+    got = P.run_score(cfg, lay, mu32, sg32, eps)
+    ref = O.scores(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), sg32.astype(np.float64), eps)
+    P.check_scores(got, ref, TOL[cfg.dtype])
+
+
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 255, 257, 2049])
+def test_score_ragged_sizes_and_capacity(n):
+    cfg = CONFIGS["c2"].with_(n_q_heads=8, n_kv_heads=2)
+    lay = make_layer(cfg, n=max(n, 8), window=8)
+    lay = dict(lay, n=n, k=np.ascontiguousarray(lay["k"][:, :, :n]), v=np.ascontiguousarray(lay["v"][:, :, :n]))
+    rmu, rsg = _oracle_stats(cfg, lay)
+    mu32, sg32 = rmu.astype(np.float32), rsg.astype(np.float32)
+    got = P.run_score(cfg, lay, mu32, sg32, 0.0, n_cap=n + 37)      # rows beyond n hold NaN
+    ref = O.scores(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), sg32.astype(np.float64), 0.0)
+    P.check_scores(got, ref, 2e-3)
+
+
+def test_score_zero_covariance_and_zero_mean():
+    cfg = CONFIGS["c2"].with_(n_q_heads=4, n_kv_heads=1)
+    lay = make_layer(cfg, n=600, window=8)
+    rmu, _ = _oracle_stats(cfg, lay)
+    mu32 = rmu.astype(np.float32)
+    z = np.zeros((1, 4, 128, 128), np.float32)
+    got = P.run_score(cfg, lay, mu32, z, 0.0)
+    ref = O.scores(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), z.astype(np.float64), 0.0)
+    P.check_scores(got, ref, 2e-3)
+    got0 = P.run_score(cfg, lay, np.zeros_like(mu32), z, 0.02)      # uniform attention 1/n
+    vn = np.linalg.norm(widen(lay["v"]), axis=-1)
+    P.check_scores(got0, (1.0 / 600 + 0.02) * vn, 2e-3)
+
+
+def test_score_c2_full_size():
+    cfg = CONFIGS["c2"]
+    lay = make_layer(cfg)
+    rmu, rsg = _oracle_stats(cfg, lay)
+    mu32, sg32 = rmu.astype(np.float32), rsg.astype(np.float32)
+    for eps in (0.02, 0.0):
+        got = P.run_score(cfg, lay, mu32, sg32, eps)
+        ref = O.scores(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), sg32.astype(np.float64), eps)
+        P.check_scores(got, ref, 2e-3)
+
+
+# ------------------------------------------------------------------------------ ea_select
+@pytest.mark.parametrize("n,n_keep", [(1, 1), (1, 0), (5, 3), (4096, 2048), (4097, 1), (5000, 4999),
+                                      (5000, 5000), (20000, 7), (70000, 35000)])
+def test_select_exact(n, n_keep):
+    cfg = CONFIGS["c2"].with_(batch=2, n_kv_heads=3, n_q_heads=3)
+    r = np.random.default_rng(n * 7 + n_keep)
+    sc = np.exp(r.standard_normal((2, 3, n))).astype(np.float32)
+    sc[0, 0] = np.float32(0.5)                                       # every score equal
+    sc[0, 1] = r.integers(0, 5, n).astype(np.float32)                # few distinct values, zeros
+    sc[1, 0, ::3] = sc[1, 0, 0]                                      # ties at one value
+    sc[1, 1] = np.sort(sc[1, 1])                                     # best pairs at the tail
+    sc[1, 2] = np.sort(sc[1, 2])[::-1]                               # best pairs at the head
+    got = P.run_select(cfg, sc, n_keep)
+    assert np.array_equal(got.astype(np.int64), O.select(sc.astype(np.float64), n_keep))
+
+
+def test_select_denormal_and_huge_scores():
+    cfg = CONFIGS["c2"].with_(batch=1, n_kv_heads=1, n_q_heads=1)
+    r = np.random.default_rng(3)
+    sc = np.concatenate([r.random(3000) * 1e-42, r.random(3000) * 3e38, [0.0] * 50]).astype(np.float32)
+    sc = r.permutation(sc)[None, None]
+    for kk in (1, 3000, 3025, 6049):
+        got = P.run_select(cfg, sc, kk)
+        assert np.array_equal(got.astype(np.int64), O.select(sc.astype(np.float64), kk))
+
+
+# ----------------------------------------------------------------------------- ea_compact
+def _masks(n, r):
+    yield "half_random", np.sort(r.choice(n, n // 2, replace=False))
+    yield "tail_only", np.arange(n - n // 3, n)
+    yield "head_only", np.arange(n // 3)
+    yield "everything", np.arange(n)
+    yield "alternate", np.arange(1, n, 2)
+    yield "shift_by_one", np.arange(1, n)
+    yield "prefix_then_gap", np.concatenate([np.arange(n // 4), np.arange(n // 2, n)])
+    yield "single_last", np.array([n - 1])
+
+
+@pytest.mark.parametrize("inplace", [True, False])
+@pytest.mark.parametrize("shape", ["d128bf16", "d256bf16", "d64f32", "d64bf16"])
+def test_compact_bit_exact(shape, inplace):
+    cfg = {"d128bf16": CONFIGS["c2"].with_(n_kv_heads=2, n_q_heads=2),
+           "d256bf16": CONFIGS["c4"].with_(batch=1, n_kv_heads=2, n_q_heads=2),
+           "d64f32": CONFIGS["c1"],
+           "d64bf16": CONFIGS["c2"].with_(head_dim=64, n_kv_heads=2, n_q_heads=2)}[shape]
+    n, n_cap = 3001, 3100
+    r = np.random.default_rng(11)
+    B, H, d = cfg.batch, cfg.n_kv_heads, cfg.head_dim
+    if cfg.dtype == "bf16":
+        k = r.integers(0, 2 ** 16, (B, H, n_cap, d)).astype(np.uint16)
+        v = r.integers(0, 2 ** 16, (B, H, n_cap, d)).astype(np.uint16)
+    else:
+        k = r.standard_normal((B, H, n_cap, d)).astype(np.float32)
+        v = r.standard_normal((B, H, n_cap, d)).astype(np.float32)
+    for name, m in _masks(n, r):
+        idx = np.broadcast_to(m, (B, H, len(m))).copy()
+        if name == "half_random":                       # a different mask per head
+            for b in range(B):
+                for h in range(H):
+                    idx[b, h] = np.sort(r.choice(n, len(m), replace=False))
+        ko, vo = P.run_compact(cfg, k, v, n, idx, inplace=inplace)
+        P.check_compaction(ko, vo, k, v, idx, len(m))
+        if inplace:                                     # rows past n_keep are left alone
+            assert np.array_equal(ko[:, :, len(m):], k[:, :, len(m):]), name
+            assert np.array_equal(vo[:, :, len(m):], v[:, :, len(m):]), name
+
+
+def test_compact_large_in_place_hazards():
+    # many chunks, strongly overlapping source/destination ranges
+    cfg = CONFIGS["c2"].with_(n_kv_heads=4, n_q_heads=4)
+    n = 40000
+    r = np.random.default_rng(12)
+    k = r.integers(0, 2 ** 16, (1, 4, n, 128)).astype(np.uint16)
+    v = r.integers(0, 2 ** 16, (1, 4, n, 128)).astype(np.uint16)
+    idx = np.stack([np.arange(100, n),                                    # shift by 100
+                    np.sort(r.choice(n, n - 100, replace=False)),         # sparse holes
+                    np.arange(n - (n - 100), n),                          # same as shift
+                    np.concatenate([np.arange(20000), np.arange(20100, n)])])[None]
+    ko, vo = P.run_compact(cfg, k, v, n, idx, inplace=True)
+    P.check_compaction(ko, vo, k, v, idx, n - 100)
+
+
+# ---------------------------------------------------------------------- ea_compress_layer
+@pytest.mark.parametrize("eps", [0.02, 0.0])
+@pytest.mark.parametrize("name", list(MINI))
+def test_compress_layer(name, eps):
+    cfg, kw = MINI[name]
+    lay = make_layer(cfg, **kw)
+    n = lay["n"]
+    n_keep = int(n * cfg.keep)
+    got = P.run_compress_layer(cfg, lay, n_keep, epsilon=eps)
+    ref = O.compress_layer(widen(lay["q_win"]), widen(lay["k"]), widen(lay["v"]), lay["q_pos0"],
+                           lay["inv_freq"], lay["t_next"], n_keep, T=cfg.horizon_T, epsilon=eps,
+                           k_store=lay["k"], v_store=lay["v"])
+    P.check_layer(cfg, lay, got, ref, n_keep, TOL[cfg.dtype])
+
+
+@pytest.mark.parametrize("n_keep", [0, 1, 999, 1000])
+def test_compress_layer_edge_budgets(n_keep):
+    cfg = CONFIGS["c2"].with_(n_q_heads=8, n_kv_heads=2)
+    lay = make_layer(cfg, n=1000, window=32)
+    got = P.run_compress_layer(cfg, lay, n_keep)
+    ref = O.compress_layer(widen(lay["q_win"]), widen(lay["k"]), widen(lay["v"]), lay["q_pos0"],
+                           lay["inv_freq"], lay["t_next"], n_keep, T=cfg.horizon_T,
+                           epsilon=cfg.epsilon, k_store=lay["k"], v_store=lay["v"])
+    P.check_layer(cfg, lay, got, ref, n_keep, 2e-3)
+    if n_keep in (0, 1000):                         # nothing moves
+        assert np.array_equal(got["k"], lay["k"]) and np.array_equal(got["v"], lay["v"])
+
+
+def test_compress_layer_without_optional_outputs_matches():
+    cfg = CONFIGS["c2"].with_(n_q_heads=8, n_kv_heads=2)
+    lay = make_layer(cfg, n=2000, window=64)
+    a = P.run_compress_layer(cfg, lay, 1000)
+    b = P.run_compress_layer(cfg, lay, 1000, want_scores=False, want_idx=False)
+    assert np.array_equal(a["k"], b["k"]) and np.array_equal(a["v"], b["v"])
+
+
+def test_compress_layer_c2_full_size():
+    cfg = CONFIGS["c2"]
+    lay = make_layer(cfg)
+    n_keep = cfg.n_keep
+    for eps in (0.02, 0.0):
+        got = P.run_compress_layer(cfg, lay, n_keep, epsilon=eps)
+        ref = O.compress_layer(widen(lay["q_win"]), widen(lay["k"]), widen(lay["v"]), lay["q_pos0"],
+                               lay["inv_freq"], lay["t_next"], n_keep, T=cfg.horizon_T, epsilon=eps,
+                               k_store=lay["k"], v_store=lay["v"])
+        P.check_layer(cfg, lay, got, ref, n_keep, 2e-3)
