@@ -40,7 +40,7 @@ __device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
   auto cv = [](uint32_t w) {
     return __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
   };
-  auto a = cv(r.x), b = cv(r.y), c = cv(r.z), d = cv(r.w);
+  auto a = cv(r[0]), b = cv(r[1]), c = cv(r[2]), d = cv(r[3]);
   half8 o;
   o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
   o[4] = c[0]; o[5] = c[1]; o[6] = d[0]; o[7] = d[1];
@@ -48,9 +48,12 @@ __device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
 }
 
 __device__ __forceinline__ float sumsq_bf16x8(u32x4 r) {
+  // plain scalar copies first: __builtin_bit_cast applied directly to a vector-element
+  // expression (r.y ...) reads element 0 of the vector
+  const uint32_t w0 = r[0], w1 = r[1], w2 = r[2], w3 = r[3];
+  const bf16x2 a = __builtin_bit_cast(bf16x2, w0), b = __builtin_bit_cast(bf16x2, w1);
+  const bf16x2 c = __builtin_bit_cast(bf16x2, w2), d = __builtin_bit_cast(bf16x2, w3);
   float s = 0.f;
-  bf16x2 a = __builtin_bit_cast(bf16x2, r.x), b = __builtin_bit_cast(bf16x2, r.y);
-  bf16x2 c = __builtin_bit_cast(bf16x2, r.z), d = __builtin_bit_cast(bf16x2, r.w);
   s = __builtin_amdgcn_fdot2_f32_bf16(a, a, s, false);
   s = __builtin_amdgcn_fdot2_f32_bf16(b, b, s, false);
   s = __builtin_amdgcn_fdot2_f32_bf16(c, c, s, false);
