@@ -104,6 +104,19 @@ ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t windo
                             int64_t n_cap, int64_t n_keep, float* scores_out, int32_t* idx_out,
                             void* ws, size_t ws_bytes, void* stream);
 
+/* Profiling aid, not part of the serving path: the same work as ea_compress_layer (without the
+ * optional outputs), with a HIP event recorded on `stream` between stages.  It creates and
+ * destroys the events, WAITS for the layer to finish, and writes the milliseconds of each
+ * stage to stage_ms (HOST pointer, EA_N_STAGES floats):
+ *   0 clear + rotary table + statistics   1 matrix-core operand preparation
+ *   2 score pass A (K/V streaming kernel)  3 score pass B (normalise, weight by ||v||)
+ *   4 selection                            5 compaction */
+#define EA_N_STAGES 6
+ea_status ea_compress_layer_timed(const ea_params* p, const void* q_win, int64_t window,
+                                  int64_t q_pos0, const double* inv_freq, int64_t t_next, void* k,
+                                  void* v, int64_t n, int64_t n_cap, int64_t n_keep, void* ws,
+                                  size_t ws_bytes, void* stream, float* stage_ms);
+
 /* Listing 1: int(n * (1 - ratio)) in IEEE double, truncated toward zero; -1 if ratio is
  * outside [0, 1] or n < 0.  Host only. */
 int64_t ea_n_keep(int64_t n, double ratio);

@@ -52,6 +52,9 @@ def load_library():
     lib.ea_compact.argtypes = [P, VP, VP, I64, I64, VP, I64, VP, VP, VP, SZ, VP]
     lib.ea_compress_layer.restype = ctypes.c_int
     lib.ea_compress_layer.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, VP, VP, SZ, VP]
+    lib.ea_compress_layer_timed.restype = ctypes.c_int
+    lib.ea_compress_layer_timed.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, SZ, VP,
+                                            ctypes.POINTER(ctypes.c_float)]
     lib.ea_n_keep.restype = I64
     lib.ea_n_keep.argtypes = [I64, ctypes.c_double]
     lib.ea_status_string.restype = ctypes.c_char_p
@@ -134,3 +137,19 @@ def compress_layer(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n
                                             int(n_cap), int(n_keep_), _ptr(scores_out),
                                             _ptr(idx_out), _ptr(ws), _nbytes(ws), _stream(stream)),
            "ea_compress_layer")
+
+
+N_STAGES = 6
+STAGE_NAMES = ("stats", "prep", "score_a", "score_b", "select", "compact")
+
+
+def compress_layer_timed(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep_, ws,
+                         stream=None):
+    """Profiling variant: returns the six stage times in milliseconds (host floats)."""
+    ms = (ctypes.c_float * N_STAGES)()
+    _check(load_library().ea_compress_layer_timed(ctypes.byref(p), _ptr(q_win), int(window),
+                                                  int(q_pos0), _ptr(inv_freq), int(t_next), _ptr(k),
+                                                  _ptr(v), int(n), int(n_cap), int(n_keep_), _ptr(ws),
+                                                  _nbytes(ws), _stream(stream), ms),
+           "ea_compress_layer_timed")
+    return list(ms)

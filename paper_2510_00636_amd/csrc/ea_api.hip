@@ -43,23 +43,28 @@ static ea_status run_stats(const Dims& d, const void* q_win, int64_t window, int
   return EA_OK;
 }
 
-// hist0 != nullptr: the finalize pass also fills the first radix-select histogram
+// hist0 != nullptr: the finalize pass also fills the first radix-select histogram.
+// ev (nullable): ev[0] is recorded after the operand preparation, ev[1] after pass A.
 static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                            const float* mu, const float* sigma, float* scores, uint32_t* hist0,
-                           char* ws, const WsLayout& L, hipStream_t st) {
+                           char* ws, const WsLayout& L, hipStream_t st, hipEvent_t* ev = nullptr) {
   float* vnorm = (float*)(ws + L.vnorm);
   if (d.dtype == EA_BF16) {
     ScorePlan sp = make_score_plan(d, n, device_num_cu());
     uint4* frags = (uint4*)(ws + L.frags);
     float* post = (float*)(ws + L.post);
     EA_TRY(launch_prep_frags(d, sp, mu, sigma, frags, post, st));
+    if (ev) EA_TRY(hipEventRecord(ev[0], st));
     EA_TRY(launch_score_mfma(d, sp, k, v, n, n_cap, frags, post, (float*)(ws + L.logits), vnorm,
                              (float2*)(ws + L.part), st));
+    if (ev) EA_TRY(hipEventRecord(ev[1], st));
     EA_TRY(launch_finalize(d, n, ws + L.logits, 0, vnorm, ws + L.part, sp.nchunk, scores, hist0, st));
   } else {
     int nchunk = 0;
+    if (ev) EA_TRY(hipEventRecord(ev[0], st));
     EA_TRY(launch_score_f32(d, k, v, n, n_cap, mu, sigma, (double*)(ws + L.logits), vnorm,
                             (double2*)(ws + L.part), &nchunk, st));
+    if (ev) EA_TRY(hipEventRecord(ev[1], st));
     EA_TRY(launch_finalize(d, n, ws + L.logits, 1, vnorm, ws + L.part, nchunk, scores, hist0, st));
   }
   return EA_OK;
@@ -147,10 +152,11 @@ ea_status ea_compact(const ea_params* p, const void* k, const void* v, int64_t n
   return EA_OK;
 }
 
-ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
-                            const double* inv_freq, int64_t t_next, void* k, void* v, int64_t n,
-                            int64_t n_cap, int64_t n_keep, float* scores_out, int32_t* idx_out,
-                            void* ws, size_t ws_bytes, void* stream) {
+static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t window,
+                               int64_t q_pos0, const double* inv_freq, int64_t t_next, void* k,
+                               void* v, int64_t n, int64_t n_cap, int64_t n_keep, float* scores_out,
+                               int32_t* idx_out, void* ws, size_t ws_bytes, void* stream,
+                               hipEvent_t* ev) {
   Dims d;
   ea_status s = check_params(p, &d);
   if (s != EA_OK) return s;
@@ -173,18 +179,53 @@ ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t windo
   int32_t* idx = idx_out ? idx_out : (int32_t*)(w + L.idx);
   uint32_t* hist = (uint32_t*)(w + L.hist);
   uint32_t* flags = (uint32_t*)(w + L.flags);
+  if (ev) EA_TRY(hipEventRecord(ev[0], st));
   // hist .. flags are adjacent regions of ws: one clearing launch covers histograms, block
   // counts and the compaction flags
   const size_t clear_words = (L.flags - L.hist) / 4 + flag_words(d, n_keep);
   EA_TRY(launch_zero(hist, clear_words, st));
   if ((s = run_stats(d, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, w, L, st)) != EA_OK)
     return s;
-  if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores, n_keep > 0 ? hist : nullptr, w, L, st)) != EA_OK)
+  if (ev) EA_TRY(hipEventRecord(ev[1], st));
+  if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores, n_keep > 0 ? hist : nullptr, w, L, st,
+                     ev ? ev + 2 : nullptr)) != EA_OK)
     return s;
-  if (n_keep == 0) return EA_OK;
-  EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, (uint32_t*)(w + L.blk), true, st));
-  EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k, v, flags, st));
+  if (ev) EA_TRY(hipEventRecord(ev[4], st));
+  if (n_keep > 0)
+    EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, (uint32_t*)(w + L.blk), true, st));
+  if (ev) EA_TRY(hipEventRecord(ev[5], st));
+  if (n_keep > 0) EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k, v, flags, st));
+  if (ev) EA_TRY(hipEventRecord(ev[6], st));
   return EA_OK;
+}
+
+ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                            const double* inv_freq, int64_t t_next, void* k, void* v, int64_t n,
+                            int64_t n_cap, int64_t n_keep, float* scores_out, int32_t* idx_out,
+                            void* ws, size_t ws_bytes, void* stream) {
+  return compress_impl(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep,
+                       scores_out, idx_out, ws, ws_bytes, stream, nullptr);
+}
+
+ea_status ea_compress_layer_timed(const ea_params* p, const void* q_win, int64_t window,
+                                  int64_t q_pos0, const double* inv_freq, int64_t t_next, void* k,
+                                  void* v, int64_t n, int64_t n_cap, int64_t n_keep, void* ws,
+                                  size_t ws_bytes, void* stream, float* stage_ms) {
+  if (!stage_ms) return EA_ERR_INVALID_ARG;
+  hipEvent_t ev[EA_N_STAGES + 1];
+  int made = 0;
+  ea_status s = EA_OK;
+  for (; made <= EA_N_STAGES; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) { s = EA_ERR_DEVICE; break; }
+  if (s == EA_OK)
+    s = compress_impl(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep, nullptr,
+                      nullptr, ws, ws_bytes, stream, ev);
+  if (s == EA_OK && hipEventSynchronize(ev[EA_N_STAGES]) != hipSuccess) s = EA_ERR_DEVICE;
+  if (s == EA_OK)
+    for (int i = 0; i < EA_N_STAGES; ++i)
+      if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) s = EA_ERR_DEVICE;
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return s;
 }
 
 }  // extern "C"

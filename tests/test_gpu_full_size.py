@@ -1,0 +1,43 @@
+"""Full-size parity in the launch configuration bench.py times: one layer of the
+Llama-3.1-8B-shaped 131072-token cache (8 KV heads, 32 query heads, d 128, window 128, keep
+50 %), generated on the device and downloaded so the oracle sees the same bits.  The oracle
+is fast enough here to check every one of the 1,048,576 scores, the kept sets and the
+compacted bytes, not just a sample."""
+import numpy as np
+import pytest
+
+from ea_inputs import CONFIGS, widen
+from oracle import ea_oracle as O
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("ratio,eps", [(0.5, 0.02), (0.75, 0.0), (0.25, 0.02)])
+def test_c3_layer_full_size(ratio, eps):
+    import torch
+    import paper_2510_00636_amd as ea
+    from ea_inputs.device import make_layer_device
+    cfg = CONFIGS["c3"]
+    lay = make_layer_device(cfg, layer=int(ratio * 100) % 32)
+    n, w = lay["n"], lay["window"]
+    n_keep = ea.n_keep(n, ratio)
+    host = dict(q_win=P.to_host(lay["q_win"]), k=P.to_host(lay["k"]), v=P.to_host(lay["v"]))
+    p = ea.make_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, ea.EA_BF16,
+                       horizon_T=cfg.horizon_T, epsilon=eps)
+    ws = torch.empty(ea.workspace_bytes(p, n, w), dtype=torch.uint8, device="cuda")
+    sc = torch.empty(cfg.batch, cfg.n_kv_heads, n, dtype=torch.float32, device="cuda")
+    idx = torch.empty(cfg.batch, cfg.n_kv_heads, n_keep, dtype=torch.int32, device="cuda")
+    ea.compress_layer(p, lay["q_win"], w, lay["q_pos0"], lay["inv_freq"], lay["t_next"], lay["k"],
+                      lay["v"], n, n, n_keep, sc, idx, ws)
+    torch.cuda.synchronize()
+    got = dict(scores=sc.cpu().numpy(), idx=idx.cpu().numpy(), k=P.to_host(lay["k"]), v=P.to_host(lay["v"]))
+    inv = lay["inv_freq"].cpu().numpy()
+    ref = O.compress_layer(widen(host["q_win"]), widen(host["k"]), widen(host["v"]), lay["q_pos0"], inv,
+                           lay["t_next"], n_keep, T=cfg.horizon_T, epsilon=eps)
+    P.check_scores(got["scores"], ref["scores"], 2e-3)
+    P.check_idx_vs_oracle_scores(got["idx"], ref["scores"], n_keep, 2e-3)
+    P.check_idx_exact_given_scores(got["idx"], got["scores"], n_keep)
+    P.check_compaction(got["k"], got["v"], host["k"], host["v"], got["idx"], n_keep)
+    # rows past n_keep are untouched
+    assert np.array_equal(got["k"][:, :, n_keep:], host["k"][:, :, n_keep:])
