@@ -77,7 +77,9 @@ ea_status ea_query_stats(const ea_params* p, const void* q_win, int64_t window, 
 /* Eq. 7-9 with ||v|| for ||W_o v|| (Sec. 3.1, implementation details) and the GQA group mean:
  *   l[g,i] = mu_g.k_i/sqrt(d) + k_i^T sigma_g k_i/(2d);  a[g,.] = softmax_i l[g,.];
  *   scores[h,i] = (mean_{g in group h} a[g,i] + epsilon) * ||v_i||_2.
- * Reads k, v rows < n once.  n >= 1. */
+ * sigma must be a covariance matrix (positive semi-definite up to rounding; it need not be
+ * exactly symmetric): its diagonal is taken as the bound of its entries when it is scaled
+ * into fp16 range for the matrix cores.  Reads k, v rows < n once.  n >= 1. */
 ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
                    const float* mu, const float* sigma, float* scores,
                    void* ws, size_t ws_bytes, void* stream);

@@ -25,7 +25,8 @@ class EaParams(ctypes.Structure):
 
 
 def lib_path():
-    return os.path.join(_HERE, "libea.so")
+    """In-tree libea.so; the environment variable EA_LIBRARY names another build of it."""
+    return os.environ.get("EA_LIBRARY") or os.path.join(_HERE, "libea.so")
 
 
 def load_library():

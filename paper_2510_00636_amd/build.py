@@ -30,7 +30,12 @@ def _compile(src):
     return obj, warn
 
 
-def build_lib(verbose=True):
+def build_lib(verbose=True, extra_flags=(), out=None):
+    global FLAGS, LIB, OBJ
+    if extra_flags or out:
+        FLAGS = FLAGS + list(extra_flags)
+        LIB = out or LIB
+        OBJ = os.path.join(OBJ, "variant_" + os.path.basename(LIB))
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 2)) as ex:
         res = list(ex.map(_compile, SOURCES))

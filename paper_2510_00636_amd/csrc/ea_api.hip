@@ -72,7 +72,7 @@ static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t 
 
 static size_t hist_words(const Dims& d) { return (size_t)d.units() * 3 * kSelBins; }
 static size_t flag_words(const Dims& d, int64_t n_keep) {
-  return 2 * (size_t)d.units() * ((n_keep + kCompactRows - 1) / kCompactRows) + 1;
+  return 2 * (size_t)d.units() * ((n_keep + kCompactRows - 1) / kCompactRows + 64);
 }
 
 }  // namespace ea

@@ -1,7 +1,7 @@
 // Gather / compaction of K and V (Listing 1: keys[indices], values[indices]).
 //
 // Row idx[j] of each (unit, tensor) moves to row j.  idx is strictly ascending, so idx[j] >= j:
-// a row only ever moves toward the front.  Work is cut into chunks of 64 destination rows.
+// a row only ever moves toward the front.  Work is cut into chunks of kCompactRows destination rows.
 // A chunk first loads all of its source rows into registers, then stores them.
 //
 // In place, chunk c's destination rows [j0, j1) may be source rows of an earlier chunk c' < c
@@ -10,7 +10,7 @@
 // Each chunk publishes a "loaded" flag right after its loads complete -- a step that waits on
 // nothing -- and chunk c polls the flags of the contiguous range of earlier chunks whose
 // source interval [idx[first], idx[last]] meets [j0, j1); the range is found with a 64-ary
-// search over idx.  Chunk numbers are handed out by an atomic ticket, so every chunk a
+// search over idx.  Chunk numbers are handed out by atomic tickets, so every chunk a
 // workgroup waits on is already running: the wait always ends.
 #include <hip/hip_runtime.h>
 
@@ -19,14 +19,17 @@
 namespace ea {
 
 constexpr int kCompactSpinLimit = 1 << 20;
+constexpr int kTicketStride = 64;   // words between the ticket counters of two tensors
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in VGPRs
 
 struct CompactArgs {
-  const uint4* src[2];
-  uint4* dst[2];
+  const u32x4* src[2];
+  u32x4* dst[2];
   const int32_t* idx;
   long long n_cap;
   int n, n_keep, units, nch;
-  uint32_t* flags;    // [2*units*nch] loaded flags, then [1] ticket
+  uint32_t* flags;    // [2*units][nch] loaded flags, then [2*units][kTicketStride] ticket counters
   int inplace;
 };
 
@@ -52,54 +55,76 @@ __device__ int first_true(int c, int lane, Pred pred) {
   return hi;
 }
 
-// RB = row bytes.  256 threads move 64 rows: RB/64 16-byte pieces per thread.
+// RB = row bytes.  Four mover wavefronts carry kCompactRows rows (RB/32 16-byte pieces per
+// thread); a fifth, control, wavefront takes the ticket, finds the chunks to wait for while
+// the movers' loads are in flight, publishes this chunk's flag and polls the others.
+//
+// Tickets are per (unit, tensor): a workgroup serves tensor blockIdx % (2*units) and draws its
+// chunk number from that tensor's own counter.  Hazards only exist inside one tensor, so the
+// "everything I wait for is already running" argument holds per counter, and the counters
+// (one per tensor, in separate cache lines) are not a serial bottleneck the way one global
+// counter is.
 template <int RB>
-__global__ __launch_bounds__(256) void k_compact(CompactArgs a) {
+__global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   constexpr int CPR = RB / 16;                 // 16-byte pieces per row
   constexpr int NLD = kCompactRows * CPR / 256;
-  __shared__ int s_id;
-  const int tid = threadIdx.x;
+  __shared__ int s_c, s_lo, s_hi;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool control = wave == 4;
   const int ntu = 2 * a.units;
-  if (tid == 0) s_id = a.inplace ? (int)atomicAdd(&a.flags[(size_t)ntu * a.nch], 1u) : (int)blockIdx.x;
+  const int tu = blockIdx.x % ntu;
+  uint32_t* flag = a.flags + (size_t)tu * a.nch;
+  if (control && lane == 0) {
+    uint32_t* ticket = a.flags + (size_t)ntu * a.nch + (size_t)tu * kTicketStride;
+    s_c = a.inplace ? (int)atomicAdd(ticket, 1u) : (int)(blockIdx.x / ntu);
+    s_lo = 0;
+    s_hi = -1;
+  }
   __syncthreads();
-  const int id = s_id;
-  const int tu = id % ntu, c = id / ntu;
+  const int c = s_c;
   const int unit = tu >> 1, tensor = tu & 1;
   const int j0 = c * kCompactRows, j1 = min(j0 + kCompactRows, a.n_keep);
   const int32_t* idx = a.idx + (size_t)unit * a.n_keep;
-  const uint4* src = a.src[tensor] + (size_t)unit * a.n_cap * CPR;
-  uint4* dst = a.dst[tensor] + (size_t)unit * a.n_cap * CPR;
+  const u32x4* src = a.src[tensor] + (size_t)unit * a.n_cap * CPR;
+  u32x4* dst = a.dst[tensor] + (size_t)unit * a.n_cap * CPR;
   // rows are strictly ascending with idx[j] >= j, so idx[j1-1] == j1-1 means nothing moves
   const bool identity = a.inplace && idx[j1 - 1] == j1 - 1;
 
-  uint4 buf[NLD];
-  if (!identity) {
+  u32x4 buf[NLD];
+  if (!control) {
+    if (!identity) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int e = tid + 256 * i, row = e / CPR, col = e % CPR;
-      // a malformed index can never leave the tensor: clamp to [0, n)
-      if (j0 + row < j1) buf[i] = src[(size_t)min(max(idx[j0 + row], 0), a.n - 1) * CPR + col];
+      for (int i = 0; i < NLD; ++i) {
+        const int e = tid + 256 * i, row = e / CPR, col = e % CPR;
+        // a malformed index can never leave the tensor: clamp to [0, n)
+        if (j0 + row < j1) buf[i] = src[(size_t)min(max(idx[j0 + row], 0), a.n - 1) * CPR + col];
+      }
     }
+    if (a.inplace) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // rows are in registers
+  } else if (a.inplace && !identity) {
+    // earlier chunks c' whose sources [idx[first], idx[last]] meet my rows [j0, j1)
+    const int lo = first_true(c, lane, [&](int x) { return idx[x * kCompactRows + kCompactRows - 1] >= j0; });
+    const int hi = first_true(c, lane, [&](int x) { return idx[x * kCompactRows] >= j1; }) - 1;
+    if (lane == 0) { s_lo = lo; s_hi = hi; }
   }
   if (a.inplace) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();                                    // every row of this chunk is in registers
-    uint32_t* flag = a.flags + (size_t)tu * a.nch;
-    if (tid == 0) __hip_atomic_store(&flag[c], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    if (!identity && tid < 64) {
-      // earlier chunks c' whose sources [idx[64c'], idx[64c'+63]] meet my rows [j0, j1)
-      const int lo = first_true(c, tid, [&](int x) { return idx[x * kCompactRows + kCompactRows - 1] >= j0; });
-      const int hi = first_true(c, tid, [&](int x) { return idx[x * kCompactRows] >= j1; }) - 1;
-      // The awaited chunks hold lower tickets, so they are running and will publish; the
-      // spin bound only makes sure that a malformed idx cannot turn into a hang.
-      for (int cc = lo + tid; cc <= hi; cc += 64)
+    __syncthreads();                 // every mover's loads have landed
+    if (control) {
+      // Relaxed, device-scope flag: what it guards are this chunk's *loads*, which have
+      // already returned, so nothing has to be flushed before it (a release would write back
+      // this XCD's L2 on every chunk).
+      if (lane == 0) __hip_atomic_store(&flag[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // The awaited chunks hold lower tickets of the same counter, so they are running and
+      // will publish; the spin bound only keeps a malformed idx from turning into a hang.
+      for (int cc = s_lo + lane; cc <= s_hi; cc += 64)
         for (int spin = 0; spin < kCompactSpinLimit &&
-             __hip_atomic_load(&flag[cc], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0u; ++spin)
+             __hip_atomic_load(&flag[cc], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u; ++spin)
           __builtin_amdgcn_s_sleep(4);
     }
-    __syncthreads();
+    __syncthreads();                 // stores are issued only after every awaited flag was seen
   }
-  if (!identity) {
+  if (!control && !identity) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int e = tid + 256 * i, row = e / CPR, col = e % CPR;
@@ -113,10 +138,10 @@ hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n
                           uint32_t* flags, hipStream_t st) {
   CompactArgs a;
   a.n = (int)n;
-  a.src[0] = (const uint4*)k;
-  a.src[1] = (const uint4*)v;
-  a.dst[0] = (uint4*)k_out;
-  a.dst[1] = (uint4*)v_out;
+  a.src[0] = (const u32x4*)k;
+  a.src[1] = (const u32x4*)v;
+  a.dst[0] = (u32x4*)k_out;
+  a.dst[1] = (u32x4*)v_out;
   a.idx = idx;
   a.n_cap = n_cap;
   a.n_keep = (int)n_keep;
@@ -127,10 +152,10 @@ hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n
   const int rb = d.D * d.esize();
   const unsigned grid = 2u * a.units * a.nch;
   switch (rb) {
-    case 128: k_compact<128><<<grid, 256, 0, st>>>(a); break;
-    case 256: k_compact<256><<<grid, 256, 0, st>>>(a); break;
-    case 512: k_compact<512><<<grid, 256, 0, st>>>(a); break;
-    case 1024: k_compact<1024><<<grid, 256, 0, st>>>(a); break;
+    case 128: k_compact<128><<<grid, 320, 0, st>>>(a); break;
+    case 256: k_compact<256><<<grid, 320, 0, st>>>(a); break;
+    case 512: k_compact<512><<<grid, 320, 0, st>>>(a); break;
+    case 1024: k_compact<1024><<<grid, 320, 0, st>>>(a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -92,7 +92,7 @@ WsLayout make_ws_layout(const Dims& d, int64_t n, int64_t window) {
   size_t nblk = ((size_t)n + kSelBlock - 1) / kSelBlock;
   w.blk = take(un * nblk * 2 * sizeof(uint32_t));
   size_t nch = ((size_t)n + kCompactRows - 1) / kCompactRows;
-  w.flags = take((2 * un * nch + 64) * sizeof(uint32_t));
+  w.flags = take(2 * un * (nch + 64) * sizeof(uint32_t));   // flags + ticket counters
   w.total = o;
   return w;
 }

@@ -12,6 +12,10 @@
 
 #include "ea_kernels.h"
 
+#ifndef EA_SCORE_SCHED_BARRIER
+#define EA_SCORE_SCHED_BARRIER 1
+#endif
+
 namespace ea {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -61,6 +65,24 @@ __device__ __forceinline__ float sumsq_bf16x8(u32x4 r) {
   return s;
 }
 
+// x + (x of another lane of the same 16-lane row), selected by a DPP control word
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
+  return x + __int_as_float(y);
+}
+
+// Sum over aligned groups of N consecutive lanes (N = 8, 16 or 32); every lane gets the total.
+template <int N>
+__device__ __forceinline__ float group_sum(float x) {
+  x = dpp_add<0xB1>(x);                       // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                       // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);                      // row_half_mirror: lanes 0-7 <-> 7-0 of each half row
+  if (N >= 16) x = dpp_add<0x140>(x);         // row_mirror
+  if (N >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
 // merge two online-softmax states (m, s): value = s * exp(m)
 __device__ __forceinline__ void merge_ms(float& m, float& s, float m2, float s2) {
   float mn = fmaxf(m, m2);
@@ -105,7 +127,8 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   constexpr int RPS = 16 / RP;          // staged rows per 256 bytes (one sweep of the LDS banks)
   extern __shared__ u32x4 smem[];
   const half8* fr = reinterpret_cast<const half8*>(smem);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: lives in an SGPR
   u32x4* stg = smem + NFRAG * 64 + wave * (16 * CPR);
   float2* red = reinterpret_cast<float2*>(smem + NFRAG * 64 + NW * (16 * CPR));
 
@@ -118,7 +141,11 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 
   {  // fragments of this (unit, pass) -> LDS
     const u32x4* src = a.frags + ((size_t)unit * a.passes + pass) * NFRAG * 64;
-    for (int i = tid; i < NFRAG * 64; i += NW * 64) smem[i] = src[i];
+#pragma unroll
+    for (int it = 0; it < (NFRAG + NW - 1) / NW; ++it) {
+      const int i = tid + it * NW * 64;
+      if (i < NFRAG * 64) smem[i] = src[i];
+    }
   }
   float pq[GH], pm[GH];
 #pragma unroll
@@ -131,8 +158,12 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 
   const int r = lane & 31, hh = lane >> 5;
   const int lrow = lane / CPR, lch = lane % CPR;
-  const long long key_lo = (long long)chunk * a.span;
-  const long long key_hi = min(key_lo + (long long)a.span, a.n);
+  // Workgroup `chunk` of a unit takes the 32*NW-key blocks chunk, chunk + nchunk, ... : at any
+  // moment the workgroups of a unit stream one contiguous region, which spreads the traffic
+  // over all HBM channels (contiguous per-workgroup spans would march through memory in
+  // lock step at a fixed large stride and pile onto a few channels).
+  const long long key_stride = (long long)a.nchunk * (NW * 32);
+  const long long key_hi = a.n;
   const u32x4* kbase = a.k + (size_t)unit * a.n_cap * CPR;
   const u32x4* vbase = a.v + (size_t)unit * a.n_cap * CPR;
 
@@ -140,17 +171,35 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 #pragma unroll
   for (int g = 0; g < GH; ++g) { m_run[g] = -INFINITY; s_run[g] = 0.f; }
 
+  // One 32-key tile = NL wave-wide 16-byte loads per tensor.  Full tiles are addressed as
+  // (uniform tile base) + lane*16 + j*1024 so the address math stays on the scalar unit; only
+  // the last, ragged tile of a head clamps rows individually.
   u32x4 kraw[NL], vraw[NL];
-  long long key0 = key_lo + (long long)wave * 32;
-  // rows are clamped to n-1, so these loads are always in bounds (also for an idle wave)
+  auto load_tile = [&](long long k0) {
+    if (k0 + 32 <= a.n) {
+      const u32x4* kp = kbase + k0 * CPR;
+      const u32x4* vp = vbase + k0 * CPR;
 #pragma unroll
-  for (int j = 0; j < NL; ++j) {
-    const long long row = min(key0 + j * RPL + lrow, a.n - 1);
-    kraw[j] = kbase[row * CPR + lch];
-    vraw[j] = do_v ? vbase[row * CPR + lch] : u32x4{0u, 0u, 0u, 0u};
-  }
+      for (int j = 0; j < NL; ++j) kraw[j] = kp[j * 64 + lane];
+      if (do_v) {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) vraw[j] = vp[j * 64 + lane];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < NL; ++j) {
+        const long long row = min(k0 + j * RPL + lrow, a.n - 1);
+        kraw[j] = kbase[row * CPR + lch];
+        if (do_v) vraw[j] = vbase[row * CPR + lch];
+      }
+    }
+  };
+#pragma unroll
+  for (int j = 0; j < NL; ++j) { kraw[j] = u32x4{0u, 0u, 0u, 0u}; vraw[j] = u32x4{0u, 0u, 0u, 0u}; }
+  long long key0 = ((long long)chunk * NW + wave) * 32;
+  if (key0 < key_hi) load_tile(key0);
 
-  for (; key0 < key_hi; key0 += NW * 32) {
+  for (; key0 < key_hi; key0 += key_stride) {
     // ---- K: coalesced registers -> LDS -> MFMA B layout.  Two phases, each staging one half
     //      of every lane's k-steps for all 32 rows (half-size buffer, all lanes busy).
     half8 Kh[NKS];
@@ -178,21 +227,14 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     if (do_v) {
 #pragma unroll
       for (int j = 0; j < NL; ++j) {
-        float ss = sumsq_bf16x8(vraw[j]);
-#pragma unroll
-        for (int o = CPR / 2; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+        const float ss = group_sum<CPR>(sumsq_bf16x8(vraw[j]));
         const long long row = key0 + j * RPL + lrow;
         if (lch == 0 && row < a.n) a.vnorm[(size_t)unit * a.n + row] = sqrtf(ss);
       }
     }
     // ---- prefetch the next tile
-    const long long nkey0 = key0 + NW * 32;
-#pragma unroll
-    for (int j = 0; j < NL; ++j) {   // past the span this re-reads a clamped row; harmless
-      const long long row = min(nkey0 + j * RPL + lrow, a.n - 1);
-      kraw[j] = kbase[row * CPR + lch];
-      vraw[j] = do_v ? vbase[row * CPR + lch] : u32x4{0u, 0u, 0u, 0u};
-    }
+    const long long nkey0 = key0 + key_stride;
+    if (nkey0 < key_hi) load_tile(nkey0);
     // ---- extra tile: rows g = mu head, GH+g = mu tail (times k); 2GH+g = diagonal residual of
     //      M (times k^2/256).  Folded into per-head logit terms so the tile dies early.
     float lin[GH];
@@ -218,29 +260,40 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
       });
     }
     __builtin_amdgcn_sched_barrier(0);
-    // ---- quadratic forms on the matrix cores
+    // ---- quadratic forms on the matrix cores.  Output tile t = (head g, 32 output channels
+    //      jt).  The accumulator chain of tile t+1 is issued together with the 16-FMA dot
+    //      product of tile t, so the vector unit works in the shadow of the matrix cores.
     float partial[GH];
-    static_for<GH>([&](auto g_) {
-      constexpr int g = decltype(g_)::value;
-      partial[g] = 0.f;
-      static_for<NJT>([&](auto jt_) {
-        constexpr int jt = decltype(jt_)::value;
-        floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        constexpr int fbase = g * NF + jt * (jt + 1);
-        static_for<2 * jt + 2>([&](auto kt_) {
-          constexpr int kt = decltype(kt_)::value;
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[(fbase + kt) * 64 + lane], Kh[kt], acc, 0, 0, 0);
-        });
-        static_for<16>([&](auto v_) {
-          constexpr int v = decltype(v_)::value;
-          constexpr int x = jt * 16 + v;
-          partial[g] = fmaf(acc[v], (float)Kh[x / 8][x % 8], partial[g]);
-        });
-        // pin the dot product here: otherwise the optimiser sinks it past the following tiles
-        // and keeps every accumulator tile alive
-        asm volatile("" : "+v"(partial[g]));
-        __builtin_amdgcn_sched_barrier(0);
+    static_for<GH>([&](auto g_) { partial[decltype(g_)::value] = 0.f; });
+    constexpr int NT = GH * NJT;
+    floatx16 accb[2];
+    auto chain = [&](auto t_) {
+      constexpr int t = decltype(t_)::value;
+      constexpr int g = t / NJT, jt = t % NJT;
+      constexpr int fbase = g * NF + jt * (jt + 1);
+      floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      static_for<2 * jt + 2>([&](auto kt_) {
+        constexpr int kt = decltype(kt_)::value;
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[(fbase + kt) * 64 + lane], Kh[kt], acc, 0, 0, 0);
       });
+      accb[t & 1] = acc;
+    };
+    chain(std::integral_constant<int, 0>{});
+    static_for<NT>([&](auto t_) {
+      constexpr int t = decltype(t_)::value;
+      constexpr int g = t / NJT, jt = t % NJT;
+      if constexpr (t + 1 < NT) chain(std::integral_constant<int, t + 1>{});
+      static_for<16>([&](auto v_) {
+        constexpr int v = decltype(v_)::value;
+        constexpr int x = jt * 16 + v;
+        partial[g] = fmaf(accb[t & 1][v], (float)Kh[x / 8][x % 8], partial[g]);
+      });
+      // pin the dot product here: otherwise the optimiser sinks it past the following tiles
+      // and keeps every accumulator tile alive
+      asm volatile("" : "+v"(partial[g]));
+#if EA_SCORE_SCHED_BARRIER
+      __builtin_amdgcn_sched_barrier(0);
+#endif
     });
     const bool valid = key0 + r < a.n;
 #pragma unroll

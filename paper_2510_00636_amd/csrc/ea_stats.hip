@@ -151,6 +151,8 @@ __device__ __forceinline__ float scale_for(float maxabs) {
   return ldexpf(1.0f, sh);
 }
 
+constexpr int kPrepSplit = 16;   // workgroups per (unit, pass)
+
 template <int D>
 __global__ __launch_bounds__(256) void k_prep_frags(const float* __restrict__ mu,
                                                     const float* __restrict__ sigma, int G,
@@ -158,49 +160,41 @@ __global__ __launch_bounds__(256) void k_prep_frags(const float* __restrict__ mu
                                                     uint4* __restrict__ frags,
                                                     float* __restrict__ post) {
   constexpr int HALF = D / 2, NKS = D / 16, NJT = D / 32, NF = NJT * (NJT + 1);
-  __shared__ float s_red[256];
   __shared__ float s_scale[16];       // [2g] = sM, [2g+1] = smu   (GH <= 8)
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int unit = blockIdx.x / passes, pass = blockIdx.x % passes;
   const int g0 = pass * GH;
-  // per-head scales
-  for (int g = 0; g < GH; ++g) {
+  // Per-head scales, one wavefront per head.  Sigma is a covariance matrix, so
+  // |Sigma[a][b]| <= max_c Sigma[c][c]: the diagonal alone bounds every entry of M (<= 2x).
+  for (int g = wave; g < GH; g += 4) {
     const int gq = g0 + g;
     float mxS = 0.f, mxM = 0.f;
     if (gq < G) {
       const float* S = sigma + ((size_t)unit * G + gq) * D * D;
-      for (int e = tid; e < D * D; e += 256) mxS = fmaxf(mxS, fabsf(S[e]));
       const float* m = mu + ((size_t)unit * G + gq) * D;
-      for (int e = tid; e < D; e += 256) mxM = fmaxf(mxM, fabsf(m[e]));
+      for (int e = lane; e < D; e += 64) {
+        mxS = fmaxf(mxS, fabsf(S[(size_t)e * D + e]));
+        mxM = fmaxf(mxM, fabsf(m[e]));
+      }
     }
-    s_red[tid] = mxS;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-      if (tid < s) s_red[tid] = fmaxf(s_red[tid], s_red[tid + s]);
-      __syncthreads();
+    for (int o = 32; o >= 1; o >>= 1) {
+      mxS = fmaxf(mxS, __shfl_xor(mxS, o));
+      mxM = fmaxf(mxM, __shfl_xor(mxM, o));
     }
-    float rS = s_red[0];
-    __syncthreads();
-    s_red[tid] = mxM;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-      if (tid < s) s_red[tid] = fmaxf(s_red[tid], s_red[tid + s]);
-      __syncthreads();
-    }
-    if (tid == 0) {
-      float sM = scale_for(2.0f * rS), sm = scale_for(s_red[0]);
+    if (lane == 0) {
+      const float sM = scale_for(2.0f * mxS), sm = scale_for(mxM);
       s_scale[2 * g] = sM;
       s_scale[2 * g + 1] = sm;
-      if (gq < G) {
+      if (gq < G && blockIdx.y == 0) {
         post[((size_t)unit * G + gq) * 2 + 0] = 1.0f / (2.0f * (float)D * sM);
         post[((size_t)unit * G + gq) * 2 + 1] = 1.0f / (sqrtf((float)D) * sm);
       }
     }
-    __syncthreads();
   }
+  __syncthreads();
 
   uint4* out = frags + ((size_t)unit * passes + pass) * nfrag * 64;
-  for (int item = tid; item < nfrag * 64; item += 256) {
+  for (int item = blockIdx.y * 256 + tid; item < nfrag * 64; item += kPrepSplit * 256) {
     const int f = item >> 6, l = item & 63;
     const int rho = l & 31, hl = l >> 5;
     _Float16 h[8];
@@ -211,18 +205,27 @@ __global__ __launch_bounds__(256) void k_prep_frags(const float* __restrict__ mu
       const int kt = rem;
       const int gq = g0 + g;
       const int c_out = ((rho >> 2) & 1) * HALF + jt * 16 + 4 * (rho >> 3) + (rho & 3);
+      const int c_in0 = hl * HALF + kt * 8;
       const float sM = s_scale[2 * g];
       const float* S = sigma + ((size_t)unit * G + gq) * D * D;
+      float val[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int c_in = hl * HALF + kt * 8 + i;
-        float val = 0.f;
-        if (gq < G) {
-          val = S[(size_t)c_in * D + c_out];
-          if ((kt >> 1) < jt) val += S[(size_t)c_out * D + c_in];
+      for (int i = 0; i < 8; ++i) val[i] = 0.f;
+      if (gq < G) {
+        // the pair (c_in, c_out) and its mirror contribute the same product k_in * k_out, so the
+        // contiguous row S[c_out][c_in0 .. c_in0+7] serves for the block on and above the
+        // diagonal; blocks strictly above also take the mirrored entries S[c_in][c_out]
+        const float4 lo = *reinterpret_cast<const float4*>(S + (size_t)c_out * D + c_in0);
+        const float4 hi = *reinterpret_cast<const float4*>(S + (size_t)c_out * D + c_in0 + 4);
+        val[0] = lo.x; val[1] = lo.y; val[2] = lo.z; val[3] = lo.w;
+        val[4] = hi.x; val[5] = hi.y; val[6] = hi.z; val[7] = hi.w;
+        if ((kt >> 1) < jt) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) val[i] += S[(size_t)(c_in0 + i) * D + c_out];
         }
-        h[i] = (_Float16)(val * sM);
       }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) h[i] = (_Float16)(val[i] * sM);
     } else {
       const int fe = f - GH * NF;
       const bool is_res = fe >= NKS;
@@ -281,7 +284,7 @@ hipError_t launch_stats(const Dims& d, const void* q_win, int w, const float2* t
 
 hipError_t launch_prep_frags(const Dims& d, const ScorePlan& sp, const float* mu,
                              const float* sigma, uint4* frags, float* post, hipStream_t st) {
-  int grid = d.units() * sp.passes;
+  dim3 grid(d.units() * sp.passes, kPrepSplit);
   if (d.D == 64)
     k_prep_frags<64><<<grid, 256, 0, st>>>(mu, sigma, d.G, sp.GH, sp.passes, sp.nfrag, frags, post);
   else if (d.D == 128)
