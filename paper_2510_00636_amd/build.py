@@ -8,7 +8,7 @@ import sys
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-CSRC = os.path.join(HERE, "csrc")
+CSRC = os.environ.get("EA_CSRC") or os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libea.so")
 SOURCES = ["ea_host.cpp", "ea_api.hip", "ea_stats.hip", "ea_score.hip", "ea_select.hip",

@@ -7,6 +7,10 @@
 
 namespace ea {
 
+#ifndef EA_NW128
+#define EA_NW128 8              // wavefronts per workgroup of the d = 128 score kernel
+#endif
+
 constexpr int kMaxWindow = 4096;
 constexpr int kSelBins = 2048;        // radix-select digit width: 11 + 11 + 10 bits
 constexpr int kSelBlock = 4096;       // scores per workgroup in the select passes

@@ -44,7 +44,7 @@ ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
   const int inst64[] = {1, 2, 4, 8}, inst128[] = {1, 2, 3, 4, 5}, inst256[] = {1};
   const int* inst = d.D == 64 ? inst64 : d.D == 128 ? inst128 : inst256;
   const int ninst = d.D == 64 ? 4 : d.D == 128 ? 5 : 1;
-  s.NW = d.D == 256 ? 4 : 8;
+  s.NW = d.D == 256 ? 4 : d.D == 128 ? EA_NW128 : 8;
   const size_t stage = (size_t)s.NW * 16 * d.D * 2;
   int ghmax = 1;
   for (int i = 0; i < ninst; ++i)

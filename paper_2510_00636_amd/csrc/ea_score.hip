@@ -12,10 +12,9 @@
 
 #include "ea_kernels.h"
 
-#ifndef EA_SCORE_SCHED_BARRIER
-#define EA_SCORE_SCHED_BARRIER 1
+#ifndef EA_FRAG_PREFETCH
+#define EA_FRAG_PREFETCH 4        // LDS fragments in flight ahead of the MFMA that consumes them
 #endif
-
 namespace ea {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -101,6 +100,20 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// output tile index jt of the rem-th fragment of a head (tile jt owns fragments
+// jt*(jt+1) .. jt*(jt+1) + 2jt + 1 of the triangular tiling)
+constexpr int tri_jt(int rem) {
+  int jt = 0;
+  while (rem >= (jt + 1) * (jt + 2)) ++jt;
+  return jt;
+}
+// LDS fragment index used by matrix-core step f (the extra tile's fragments are stored last)
+template <int GH, int NF, int NX>
+constexpr int step_frag(int f) { return f < NX ? GH * NF + f : f - NX; }
+
+// The 2*NL global loads of the next tile are spread evenly over the steps [NX, NS).
+template <int NX, int NS, int NL>
+constexpr int load_slot(int i) { return NX + (i * (NS - NX)) / (2 * NL); }
 // accumulator row rho of a 32x32 tile lives in register ROW_V(rho) of the lanes with
 // lane / 32 == ROW_HH(rho)  (column = lane % 32)
 #define ROW_V(rho) (4 * ((rho) / 8) + (rho) % 4)
@@ -115,7 +128,12 @@ __device__ __forceinline__ void static_for(F&& f) {
 // loads in, conflict-free 16-byte LDS reads out); V rows are squared and summed straight
 // from the coalesced layout.  The next tile's K and V loads are issued before the matrix
 // work of the current one.
-template <int D, int GH, int NW>
+//
+// Ragged tail: the last tile of a head is moved back to start at n - 32, so it overlaps its
+// predecessor instead of running past the tensor; the keys it shares with the predecessor are
+// recomputed and masked out of the stores and of the softmax sums.  Heads shorter than one tile
+// (n < 32) use the CLAMP instance, which clamps every row index instead.
+template <int D, int GH, int NW, bool CLAMP>
 __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   constexpr int NKS = D / 16, NJT = D / 32, NF = NJT * (NJT + 1);
   constexpr int NFRAG = GH * NF + 2 * NKS;
@@ -171,14 +189,19 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 #pragma unroll
   for (int g = 0; g < GH; ++g) { m_run[g] = -INFINITY; s_run[g] = 0.f; }
 
-  // One 32-key tile = NL wave-wide 16-byte loads per tensor.  Full tiles are addressed as
-  // (uniform tile base) + lane*16 + j*1024 so the address math stays on the scalar unit; only
-  // the last, ragged tile of a head clamps rows individually.
+  // One 32-key tile = NL wave-wide 16-byte loads per tensor, addressed as (uniform tile base)
+  // + lane*16 + j*1024 so that the address arithmetic stays on the scalar unit.
   u32x4 kraw[NL], vraw[NL];
-  auto load_tile = [&](long long k0) {
-    if (k0 + 32 <= a.n) {
-      const u32x4* kp = kbase + k0 * CPR;
-      const u32x4* vp = vbase + k0 * CPR;
+  auto tile_base = [&](long long k0) -> long long {          // first row actually loaded
+    return (!CLAMP && k0 + 32 > a.n) ? a.n - 32 : k0;
+  };
+#pragma unroll
+  for (int j = 0; j < NL; ++j) { kraw[j] = u32x4{0u, 0u, 0u, 0u}; vraw[j] = u32x4{0u, 0u, 0u, 0u}; }
+  long long key0 = ((long long)chunk * NW + wave) * 32;
+  if (key0 < key_hi) {                                       // first tile: plain loads
+    if constexpr (!CLAMP) {
+      const u32x4* kp = kbase + tile_base(key0) * CPR;
+      const u32x4* vp = vbase + tile_base(key0) * CPR;
 #pragma unroll
       for (int j = 0; j < NL; ++j) kraw[j] = kp[j * 64 + lane];
       if (do_v) {
@@ -188,16 +211,35 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     } else {
 #pragma unroll
       for (int j = 0; j < NL; ++j) {
-        const long long row = min(k0 + j * RPL + lrow, a.n - 1);
+        const long long row = min(key0 + j * RPL + lrow, a.n - 1);
         kraw[j] = kbase[row * CPR + lch];
         if (do_v) vraw[j] = vbase[row * CPR + lch];
       }
     }
-  };
+  }
+
+  // Results of a tile are stored one iteration later, right after the staging of the next
+  // tile: global stores share the in-order counter of the loads, and stores issued while
+  // loads are pending make every later wait for a load also wait for the store.
+  float lg_prev[GH], vsq_prev = 0.f;
 #pragma unroll
-  for (int j = 0; j < NL; ++j) { kraw[j] = u32x4{0u, 0u, 0u, 0u}; vraw[j] = u32x4{0u, 0u, 0u, 0u}; }
-  long long key0 = ((long long)chunk * NW + wave) * 32;
-  if (key0 < key_hi) load_tile(key0);
+  for (int g = 0; g < GH; ++g) lg_prev[g] = 0.f;
+  long long key_prev = 0;
+  bool have_prev = false;
+  auto store_prev = [&]() {
+    const long long b0 = tile_base(key_prev);
+    const long long key = b0 + r;
+    if (hh == 0 && key >= key_prev && key < a.n) {
+#pragma unroll
+      for (int g = 0; g < GH; ++g)
+        if (g0 + g < a.G) a.logits[((size_t)unit * a.G + g0 + g) * a.n + key] = lg_prev[g];
+    }
+    if (do_v) {
+      const long long row = b0 + lch * RPL + lrow;
+      if (lch < NL && row >= key_prev && row < a.n)
+        a.vnorm[(size_t)unit * a.n + row] = __builtin_amdgcn_sqrtf(vsq_prev);
+    }
+  };
 
   for (; key0 < key_hi; key0 += key_stride) {
     // ---- K: coalesced registers -> LDS -> MFMA B layout.  Two phases, each staging one half
@@ -223,91 +265,124 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       __builtin_amdgcn_wave_barrier();
     }
-    // ---- V: squared norms from the coalesced layout
-    if (do_v) {
-#pragma unroll
-      for (int j = 0; j < NL; ++j) {
-        const float ss = group_sum<CPR>(sumsq_bf16x8(vraw[j]));
-        const long long row = key0 + j * RPL + lrow;
-        if (lch == 0 && row < a.n) a.vnorm[(size_t)unit * a.n + row] = sqrtf(ss);
-      }
-    }
-    // ---- prefetch the next tile
+    if (have_prev) store_prev();
+
+    // ---- where the next tile comes from.  Without a next tile the loads below still run (the
+    //      matrix-core phase is one straight-line block) but all lanes read the head's first
+    //      16 bytes: no traffic to speak of.
     const long long nkey0 = key0 + key_stride;
-    if (nkey0 < key_hi) load_tile(nkey0);
-    // ---- extra tile: rows g = mu head, GH+g = mu tail (times k); 2GH+g = diagonal residual of
-    //      M (times k^2/256).  Folded into per-head logit terms so the tile dies early.
-    float lin[GH];
+    const bool has_next = nkey0 < key_hi;
+    const u32x4* kp_n = has_next ? kbase + tile_base(nkey0) * CPR : kbase;
+    const u32x4* vp_n = (has_next && do_v) ? vbase + tile_base(nkey0) * CPR : vbase;
+    const int kl = has_next ? lane : 0, vl = (has_next && do_v) ? lane : 0;
+    const int kj = has_next ? 64 : 0, vj = (has_next && do_v) ? 64 : 0;
+
+    // ---- matrix-core phase: NS = 2*NKS + GH*NF steps, one LDS fragment and one MFMA each.
+    //   steps [0, NKS)       extra tile, rows g / GH+g = fp16 head / tail of mu, times k
+    //   steps [NKS, 2NKS)    extra tile, rows 2GH+g = rounding residual of diag(M), times k^2/256
+    //   then per output tile t = (head g, 32 output channels jt): 2jt+2 steps over the k-steps on
+    //   or below the diagonal; its accumulator is then dotted with k (16 FMAs).
+    // Everything else of the iteration rides in the shadow of the MFMAs:
+    //   * fragments are fetched PD steps ahead into a register ring;
+    //   * the 16 FMAs of tile t are issued four per step during steps end(t)+2 .. end(t)+5
+    //     (three accumulators rotate, so a tile is not rewritten before it has been read);
+    //   * the squared norm of V chunk j is formed at step j;
+    //   * the 2*NL global loads of the next tile are spread over the steps after the extra
+    //     tile, one at a time, so they never queue up in front of the memory pipeline.
+    float lin[GH], partial[GH], vsq = 0.f;
+    static_for<GH>([&](auto g_) { partial[decltype(g_)::value] = 0.f; lin[decltype(g_)::value] = 0.f; });
     {
-      floatx16 ex = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      static_for<NKS>([&](auto kt_) {
-        constexpr int kt = decltype(kt_)::value;
-        ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[(GH * NF + kt) * 64 + lane], Kh[kt], ex, 0, 0, 0);
+      constexpr int NX = 2 * NKS, NS = NX + GH * NF, NT = GH * NJT, PD = EA_FRAG_PREFETCH;
+      half8 fb[PD + 1];
+      floatx16 ex, accb[3];
+      static_for<PD>([&](auto i_) {
+        constexpr int i = decltype(i_)::value;
+        fb[i] = fr[step_frag<GH, NF, NX>(i) * 64 + lane];
       });
-      static_for<NKS>([&](auto kt_) {
-        constexpr int kt = decltype(kt_)::value;
-        half8 t = Kh[kt] * (_Float16)0.0625f;
-        t = t * t;
-        ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[(GH * NF + NKS + kt) * 64 + lane], t, ex, 0, 0, 0);
-      });
-      static_for<GH>([&](auto g_) {
-        constexpr int g = decltype(g_)::value;
-        float e = 0.f;
-        if (hh == ROW_HH(g)) e += ex[ROW_V(g)] * pm[g];
-        if (hh == ROW_HH(GH + g)) e += ex[ROW_V(GH + g)] * pm[g];
-        if (hh == ROW_HH(2 * GH + g)) e += ex[ROW_V(2 * GH + g)] * (256.0f * pq[g]);
-        lin[g] = e;
+      __builtin_amdgcn_sched_barrier(0);
+      // FMAs 4q .. 4q+3 of the dot product of tile tt
+      auto dot4 = [&](auto tt_, auto q_) {
+        constexpr int tt = decltype(tt_)::value, q = decltype(q_)::value;
+        constexpr int g = tt / NJT, jt = tt % NJT;
+        static_for<4>([&](auto v_) {
+          constexpr int v = 4 * q + decltype(v_)::value;
+          constexpr int x = jt * 16 + v;
+          partial[g] = fmaf(accb[tt % 3][v], (float)Kh[x / 8][x % 8], partial[g]);
+        });
+        // pin: otherwise the optimiser sinks the dot products to the end of the phase and keeps
+        // every accumulator tile alive
+        if constexpr (q == 3) asm volatile("" : "+v"(partial[g]));
+      };
+      static_for<NS + 6>([&](auto f_) {
+        constexpr int f = decltype(f_)::value;
+        if constexpr (f < NS) {
+          if constexpr (f + PD < NS)
+            fb[(f + PD) % (PD + 1)] = fr[step_frag<GH, NF, NX>(f + PD) * 64 + lane];
+          const half8 A = fb[f % (PD + 1)];
+          constexpr floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          if constexpr (f < NKS) {
+            ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Kh[f], f == 0 ? zero : ex, 0, 0, 0);
+          } else if constexpr (f < NX) {
+            half8 t = Kh[f - NKS] * (_Float16)0.0625f;
+            t = t * t;
+            ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, t, ex, 0, 0, 0);
+          } else {
+            constexpr int m = f - NX, g = m / NF, rem = m % NF;
+            constexpr int jt = tri_jt(rem), kt = rem - jt * (jt + 1), t = g * NJT + jt;
+            accb[t % 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Kh[kt], kt == 0 ? zero : accb[t % 3], 0, 0, 0);
+          }
+        }
+        // ---- vector work placed in this step
+        if constexpr (f < NL) {                   // V chunk f: lane lch == f keeps its row's sum
+          const float ss = group_sum<CPR>(sumsq_bf16x8(vraw[f]));
+          vsq = lch == f ? ss : vsq;
+        }
+        if constexpr (f == NX + 1) {              // rows of the extra tile, two steps after its end
+          static_for<GH>([&](auto g_) {
+            constexpr int g = decltype(g_)::value;
+            float e = 0.f;
+            if (hh == ROW_HH(g)) e += ex[ROW_V(g)] * pm[g];
+            if (hh == ROW_HH(GH + g)) e += ex[ROW_V(GH + g)] * pm[g];
+            if (hh == ROW_HH(2 * GH + g)) e += ex[ROW_V(2 * GH + g)] * (256.0f * pq[g]);
+            lin[g] = e;
+          });
+        }
+        static_for<NT>([&](auto tt_) {
+          constexpr int tt = decltype(tt_)::value;
+          constexpr int e = NX + (tt / NJT) * NF + (tt % NJT + 1) * (tt % NJT + 2) - 1;   // last step of tile tt
+          if constexpr (f >= e + 2 && f < e + 6) dot4(tt_, std::integral_constant<int, f - e - 2>{});
+        });
+        // ---- loads of the next tile that belong to this step (K first, then V)
+        static_for<2 * NL>([&](auto i_) {
+          constexpr int i = decltype(i_)::value;
+          if constexpr (f < NS && load_slot<NX, NS, NL>(i) == f) {
+            if constexpr (i < NL) kraw[i] = kp_n[i * kj + kl];
+            else vraw[i - NL] = vp_n[(i - NL) * vj + vl];
+          }
+        });
+        // Nothing may move across a step: the program order written above -- fragment read PD
+        // steps ahead, one MFMA, the vector / memory work that rides in its shadow -- is the
+        // software pipeline.  (Left alone, the scheduler sinks every LDS read next to its MFMA.)
+        __builtin_amdgcn_sched_barrier(0);
       });
     }
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- quadratic forms on the matrix cores.  Output tile t = (head g, 32 output channels
-    //      jt).  The accumulator chain of tile t+1 is issued together with the 16-FMA dot
-    //      product of tile t, so the vector unit works in the shadow of the matrix cores.
-    float partial[GH];
-    static_for<GH>([&](auto g_) { partial[decltype(g_)::value] = 0.f; });
-    constexpr int NT = GH * NJT;
-    floatx16 accb[2];
-    auto chain = [&](auto t_) {
-      constexpr int t = decltype(t_)::value;
-      constexpr int g = t / NJT, jt = t % NJT;
-      constexpr int fbase = g * NF + jt * (jt + 1);
-      floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      static_for<2 * jt + 2>([&](auto kt_) {
-        constexpr int kt = decltype(kt_)::value;
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[(fbase + kt) * 64 + lane], Kh[kt], acc, 0, 0, 0);
-      });
-      accb[t & 1] = acc;
-    };
-    chain(std::integral_constant<int, 0>{});
-    static_for<NT>([&](auto t_) {
-      constexpr int t = decltype(t_)::value;
-      constexpr int g = t / NJT, jt = t % NJT;
-      if constexpr (t + 1 < NT) chain(std::integral_constant<int, t + 1>{});
-      static_for<16>([&](auto v_) {
-        constexpr int v = decltype(v_)::value;
-        constexpr int x = jt * 16 + v;
-        partial[g] = fmaf(accb[t & 1][v], (float)Kh[x / 8][x % 8], partial[g]);
-      });
-      // pin the dot product here: otherwise the optimiser sinks it past the following tiles
-      // and keeps every accumulator tile alive
-      asm volatile("" : "+v"(partial[g]));
-#if EA_SCORE_SCHED_BARRIER
-      __builtin_amdgcn_sched_barrier(0);
-#endif
-    });
-    const bool valid = key0 + r < a.n;
+    const bool valid = tile_base(key0) + r >= key0 && tile_base(key0) + r < a.n;
 #pragma unroll
     for (int g = 0; g < GH; ++g) {
       float lg = partial[g] * pq[g] + lin[g];
       lg += __shfl_xor(lg, 32);
+      lg_prev[g] = lg;
       if (valid && g0 + g < a.G) {
-        if (hh == 0) a.logits[((size_t)unit * a.G + g0 + g) * a.n + key0 + r] = lg;
         float mn = fmaxf(m_run[g], lg);
         s_run[g] = s_run[g] * __expf(m_run[g] - mn) + __expf(lg - mn);
         m_run[g] = mn;
       }
     }
+    vsq_prev = vsq;
+    key_prev = key0;
+    have_prev = true;
   }
+  if (have_prev) store_prev();
 
   // ---- (max, sum) of this workgroup's keys, per head
 #pragma unroll
@@ -331,9 +406,9 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   }
 }
 
-template <int D, int GH, int NW>
+template <int D, int GH, int NW, bool CLAMP>
 static hipError_t launch_one(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st) {
-  auto kern = k_score_mfma<D, GH, NW>;
+  auto kern = k_score_mfma<D, GH, NW, CLAMP>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp.lds_bytes);
   if (e != hipSuccess) return e;
@@ -361,17 +436,18 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
   a.nchunk = sp.nchunk;
   a.units = d.units();
   a.nfrag = sp.nfrag;
-#define EA_CASE(DD, GG, WW) \
-  if (d.D == DD && sp.GH == GG && sp.NW == WW) return launch_one<DD, GG, WW>(a, sp, st)
+#define EA_CASE(DD, GG, WW)                                                         \
+  if (d.D == DD && sp.GH == GG && sp.NW == WW)                                      \
+  return n < 32 ? launch_one<DD, GG, WW, true>(a, sp, st) : launch_one<DD, GG, WW, false>(a, sp, st)
   EA_CASE(64, 1, 8);
   EA_CASE(64, 2, 8);
   EA_CASE(64, 4, 8);
   EA_CASE(64, 8, 8);
-  EA_CASE(128, 1, 8);
-  EA_CASE(128, 2, 8);
-  EA_CASE(128, 3, 8);
-  EA_CASE(128, 4, 8);
-  EA_CASE(128, 5, 8);
+  EA_CASE(128, 1, EA_NW128);
+  EA_CASE(128, 2, EA_NW128);
+  EA_CASE(128, 3, EA_NW128);
+  EA_CASE(128, 4, EA_NW128);
+  EA_CASE(128, 5, EA_NW128);
   EA_CASE(256, 1, 4);
 #undef EA_CASE
   return hipErrorInvalidValue;
