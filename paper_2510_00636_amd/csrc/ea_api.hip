@@ -34,11 +34,13 @@ static ea_status check_ws(const Dims& d, int64_t n, int64_t window, void* ws, si
   return EA_OK;
 }
 
+// clear / clear_words: scratch words zeroed by the table kernel on its way (may be none)
 static ea_status run_stats(const Dims& d, const void* q_win, int64_t window, int64_t q_pos0,
                            const double* inv_freq, int64_t t_next, float* mu, float* sigma,
-                           char* ws, const WsLayout& L, hipStream_t st) {
+                           char* ws, const WsLayout& L, hipStream_t st, uint32_t* clear = nullptr,
+                           size_t clear_words = 0) {
   float2* tab = (float2*)(ws + L.tab);
-  EA_TRY(launch_rope_table(d, inv_freq, q_pos0, t_next, (int)window, tab, st));
+  EA_TRY(launch_rope_table(d, inv_freq, q_pos0, t_next, (int)window, tab, clear, clear_words, st));
   EA_TRY(launch_stats(d, q_win, (int)window, tab, mu, sigma, st));
   return EA_OK;
 }
@@ -183,8 +185,8 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
   // hist .. flags are adjacent regions of ws: one clearing launch covers histograms, block
   // counts and the compaction flags
   const size_t clear_words = (L.flags - L.hist) / 4 + flag_words(d, n_keep);
-  EA_TRY(launch_zero(hist, clear_words, st));
-  if ((s = run_stats(d, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, w, L, st)) != EA_OK)
+  if ((s = run_stats(d, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, w, L, st, hist,
+                     clear_words)) != EA_OK)
     return s;
   if (ev) EA_TRY(hipEventRecord(ev[1], st));
   if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores, n_keep > 0 ? hist : nullptr, w, L, st,

@@ -8,7 +8,7 @@ namespace ea {
 
 // ea_stats.hip
 hipError_t launch_rope_table(const Dims& d, const double* inv_freq, int64_t q_pos0, int64_t t_next,
-                             int w, float2* tab, hipStream_t st);
+                             int w, float2* tab, uint32_t* clear, size_t clear_words, hipStream_t st);
 hipError_t launch_stats(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
                         float* sigma, hipStream_t st);
 hipError_t launch_prep_frags(const Dims& d, const ScorePlan& sp, const float* mu,

@@ -18,8 +18,12 @@ namespace ea {
 //   mean_j exp(i (t_next + j) theta) = exp(i theta (t_next + (T-1)/2)) sin(T theta/2) / (T sin(theta/2)).
 __global__ void k_rope_table(const double* __restrict__ inv_freq, long long q_pos0,
                              long long t_next, int T, int w, int half, int q_is_rotated,
-                             float2* __restrict__ tab) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
+                             float2* __restrict__ tab, uint32_t* __restrict__ clear,
+                             size_t clear_words) {
+  const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  // riding along: zero the counters / histograms / flags of the later stages (one launch less)
+  for (size_t i = gid; i < clear_words; i += (size_t)gridDim.x * blockDim.x) clear[i] = 0u;
+  int i = (int)gid;
   if (i >= w * half) return;
   int s = i / half, c = i - s * half;
   double th = inv_freq[c];
@@ -39,88 +43,147 @@ __global__ void k_rope_table(const double* __restrict__ inv_freq, long long q_po
   tab[i] = make_float2((float)(cb * ca + sb * sa), (float)(sb * ca - cb * sa));
 }
 
-__device__ __forceinline__ float load_q(const void* q, size_t i, int dtype) {
-  if (dtype == EA_BF16) return __uint_as_float((uint32_t)((const uint16_t*)q)[i] << 16);
-  return ((const float*)q)[i];
+// ---------------------------------------------------------------------------------------
+// One workgroup = 16 rows of one head's Sigma.  The window is processed in chunks of up to 128
+// samples: every thread issues all its 16-byte query loads and table loads of a chunk at once
+// (one memory latency per chunk instead of one per sample), writes the transformed samples
+// u~ to LDS, and the workgroup then forms column sums (first pass) or centred outer products
+// (second pass) from LDS.  A window of at most 128 samples is loaded only once.
+constexpr int kStatsRB = 16;    // Sigma rows per workgroup
+constexpr int kStatsWC = 128;   // samples per LDS chunk
+
+template <int D, bool BF16>
+__device__ __forceinline__ void stats_load_chunk(const void* __restrict__ q_win, size_t qbase, int s0,
+                                                 int ns, int layout, const float2* __restrict__ tab,
+                                                 float* __restrict__ s_u) {
+  constexpr int HALF = D / 2, G8 = HALF / 8;          // groups of 8 channel pairs per sample
+  constexpr int ITEMS = kStatsWC * G8 / 256;          // (sample, group) items per thread
+  const int tid = threadIdx.x;
+  float qa[ITEMS][8], qb[ITEMS][8];
+  float2 tb[ITEMS][8];
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) {
+    const int item = tid + it * 256, sl = item / G8, g = item % G8;
+    if (sl < ns) {
+      const size_t row = qbase + (size_t)(s0 + sl) * D;
+      // half-split: channels 8g.. and HALF+8g..; interleaved: 16 consecutive channels = 8 pairs
+      const size_t oa = row + (layout ? 16 * g : 8 * g), ob = row + (layout ? 16 * g + 8 : HALF + 8 * g);
+      float xa[8], xb[8];
+      if (BF16) {
+        const uint4 ra = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + oa);
+        const uint4 rb = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + ob);
+        const uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb.x, rb.y, rb.z, rb.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          xa[2 * e] = __uint_as_float(wa[e] << 16);
+          xa[2 * e + 1] = __uint_as_float(wa[e] & 0xffff0000u);
+          xb[2 * e] = __uint_as_float(wb[e] << 16);
+          xb[2 * e + 1] = __uint_as_float(wb[e] & 0xffff0000u);
+        }
+      } else {
+        const float4 a0 = *reinterpret_cast<const float4*>((const float*)q_win + oa);
+        const float4 a1 = *reinterpret_cast<const float4*>((const float*)q_win + oa + 4);
+        const float4 b0 = *reinterpret_cast<const float4*>((const float*)q_win + ob);
+        const float4 b1 = *reinterpret_cast<const float4*>((const float*)q_win + ob + 4);
+        xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w; xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+        xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w; xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        // pair e of the group: (xa[e], xb[e]) half-split; (x[2e], x[2e+1]) of the 16 interleaved
+        qa[it][e] = layout ? (e < 4 ? xa[2 * e] : xb[2 * e - 8]) : xa[e];
+        qb[it][e] = layout ? (e < 4 ? xa[2 * e + 1] : xb[2 * e - 7]) : xb[e];
+      }
+      const float4* tp = reinterpret_cast<const float4*>(tab + (size_t)(s0 + sl) * HALF + 8 * g);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float4 t = tp[e];
+        tb[it][2 * e] = make_float2(t.x, t.y);
+        tb[it][2 * e + 1] = make_float2(t.z, t.w);
+      }
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < ITEMS; ++it) {
+    const int item = tid + it * 256, sl = item / G8, g = item % G8;
+    if (sl < ns) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int c = 8 * g + e;
+        const int ja = layout ? 2 * c : c, jb = layout ? 2 * c + 1 : c + HALF;
+        s_u[sl * D + ja] = tb[it][e].x * qa[it][e] - tb[it][e].y * qb[it][e];
+        s_u[sl * D + jb] = tb[it][e].y * qa[it][e] + tb[it][e].x * qb[it][e];
+      }
+    }
+  }
 }
 
-// ---------------------------------------------------------------------------------------
-// One workgroup = 16 rows of one head's Sigma.  Pass 1 forms the mean of the transformed
-// samples; pass 2 walks the window in chunks of SC samples staged (centred) in LDS and
-// accumulates the outer products in fp32.
-constexpr int kStatsRB = 16;   // Sigma rows per workgroup
-constexpr int kStatsSC = 32;   // samples per LDS chunk
-
-template <int D>
-__global__ __launch_bounds__(256) void k_stats(const void* __restrict__ q_win, int dtype,
-                                               int w, int layout, int ddof,
-                                               const float2* __restrict__ tab,
-                                               float* __restrict__ mu,
-                                               float* __restrict__ sigma) {
-  constexpr int HALF = D / 2;
-  constexpr int NGRP = 256 / HALF;            // thread groups over channel pairs
-  constexpr int RG = 256 / D;                 // row groups in the accumulation phase
-  constexpr int NO = kStatsRB / RG;           // Sigma rows per thread
-  __shared__ float s_mean[D];
-  __shared__ float s_part[NGRP][D];
-  __shared__ __align__(16) float s_u[kStatsSC][D];
-
+template <int D, bool BF16>
+__global__ __launch_bounds__(256) void k_stats(const void* __restrict__ q_win, int w, int layout,
+                                               int ddof, const float2* __restrict__ tab,
+                                               float* __restrict__ mu, float* __restrict__ sigma) {
+  constexpr int RG = 256 / D > 0 ? 256 / D : 1;   // row groups in the accumulation phase
+  constexpr int NO = kStatsRB / RG;               // Sigma rows per thread
+  extern __shared__ __align__(16) float s_dyn[];
+  float* s_u = s_dyn;                             // [kStatsWC][D]
+  float* s_mean = s_dyn + kStatsWC * D;           // [D]
   const int head = blockIdx.x, rb = blockIdx.y, tid = threadIdx.x;
   const size_t qbase = (size_t)head * w * D;
-  const int c = tid % HALF, grp = tid / HALF;
-  const int ia = layout ? 2 * c : c, ib = layout ? 2 * c + 1 : c + HALF;
+  const int nchunks = (w + kStatsWC - 1) / kStatsWC;
 
-  // pass 1: column sums of the transformed samples
-  float sa = 0.f, sb = 0.f;
-  for (int s = grp; s < w; s += NGRP) {
-    float2 t = tab[s * HALF + c];
-    float qa = load_q(q_win, qbase + (size_t)s * D + ia, dtype);
-    float qb = load_q(q_win, qbase + (size_t)s * D + ib, dtype);
-    sa += t.x * qa - t.y * qb;
-    sb += t.y * qa + t.x * qb;
+  // pass 1: column sums
+  float colsum = 0.f;
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
+    if (ch > 0) __syncthreads();
+    stats_load_chunk<D, BF16>(q_win, qbase, s0, ns, layout, tab, s_u);
+    __syncthreads();
+    if (tid < D)
+      for (int sl = 0; sl < ns; ++sl) colsum += s_u[sl * D + tid];
   }
-  s_part[grp][ia] = sa;
-  s_part[grp][ib] = sb;
-  __syncthreads();
   if (tid < D) {
-    float m = 0.f;
-    for (int g = 0; g < NGRP; ++g) m += s_part[g][tid];
-    m /= (float)w;
+    const float m = colsum / (float)w;
     s_mean[tid] = m;
     if (rb == 0) mu[(size_t)head * D + tid] = m;
   }
   __syncthreads();
 
-  // pass 2: centred outer products
+  // pass 2: centred outer products (the single chunk of a short window is still in LDS)
   const int j = tid % D, rg = tid / D;
   const int i0 = rb * kStatsRB + rg * NO;
   float acc[NO];
 #pragma unroll
   for (int o = 0; o < NO; ++o) acc[o] = 0.f;
-  for (int s0 = 0; s0 < w; s0 += kStatsSC) {
-    const int ns = min(kStatsSC, w - s0);
-    for (int e = tid; e < ns * HALF; e += 256) {
-      int sl = e / HALF, cc = e - sl * HALF;
-      int ja = layout ? 2 * cc : cc, jb = layout ? 2 * cc + 1 : cc + HALF;
-      int s = s0 + sl;
-      float2 t = tab[s * HALF + cc];
-      float qa = load_q(q_win, qbase + (size_t)s * D + ja, dtype);
-      float qb = load_q(q_win, qbase + (size_t)s * D + jb, dtype);
-      s_u[sl][ja] = t.x * qa - t.y * qb - s_mean[ja];
-      s_u[sl][jb] = t.y * qa + t.x * qb - s_mean[jb];
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
+    if (nchunks > 1) {
+      __syncthreads();
+      stats_load_chunk<D, BF16>(q_win, qbase, s0, ns, layout, tab, s_u);
+      __syncthreads();
     }
+    for (int e = tid; e < ns * D; e += 256) s_u[e] -= s_mean[e % D];
     __syncthreads();
-    for (int sl = 0; sl < ns; ++sl) {
-      float xj = s_u[sl][j];
+    if (rg < RG) {
+#pragma unroll 4
+      for (int sl = 0; sl < ns; ++sl) {
+        const float xj = s_u[sl * D + j];
+        const float4* xi = reinterpret_cast<const float4*>(s_u + sl * D + i0);
 #pragma unroll
-      for (int o = 0; o < NO; ++o) acc[o] = fmaf(s_u[sl][i0 + o], xj, acc[o]);
+        for (int o4 = 0; o4 < NO / 4; ++o4) {
+          const float4 x = xi[o4];
+          acc[4 * o4 + 0] = fmaf(x.x, xj, acc[4 * o4 + 0]);
+          acc[4 * o4 + 1] = fmaf(x.y, xj, acc[4 * o4 + 1]);
+          acc[4 * o4 + 2] = fmaf(x.z, xj, acc[4 * o4 + 2]);
+          acc[4 * o4 + 3] = fmaf(x.w, xj, acc[4 * o4 + 3]);
+        }
+      }
     }
-    __syncthreads();
   }
   const float inv = 1.0f / (float)(w - ddof);
+  if (rg < RG) {
 #pragma unroll
-  for (int o = 0; o < NO; ++o)
-    sigma[((size_t)head * D + i0 + o) * D + j] = acc[o] * inv;
+    for (int o = 0; o < NO; ++o) sigma[((size_t)head * D + i0 + o) * D + j] = acc[o] * inv;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -263,23 +326,35 @@ __global__ __launch_bounds__(256) void k_prep_frags(const float* __restrict__ mu
 
 // ---------------------------------------------------------------------------------------
 hipError_t launch_rope_table(const Dims& d, const double* inv_freq, int64_t q_pos0, int64_t t_next,
-                             int w, float2* tab, hipStream_t st) {
+                             int w, float2* tab, uint32_t* clear, size_t clear_words, hipStream_t st) {
   int total = w * d.half;
   k_rope_table<<<(total + 255) / 256, 256, 0, st>>>(inv_freq, q_pos0, t_next, d.T, w, d.half,
-                                                    d.q_is_rotated, tab);
+                                                    d.q_is_rotated, tab, clear, clear_words);
+  return hipGetLastError();
+}
+
+template <int D, bool BF16>
+static hipError_t launch_stats_one(const Dims& d, const void* q_win, int w, const float2* tab,
+                                   float* mu, float* sigma, hipStream_t st) {
+  auto kern = k_stats<D, BF16>;
+  const size_t lds = (size_t)(kStatsWC * D + D) * sizeof(float);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  dim3 grid(d.qheads(), d.D / kStatsRB);
+  kern<<<grid, 256, lds, st>>>(q_win, w, d.rope_layout, d.ddof, tab, mu, sigma);
   return hipGetLastError();
 }
 
 hipError_t launch_stats(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
                         float* sigma, hipStream_t st) {
-  dim3 grid(d.qheads(), d.D / kStatsRB);
-  if (d.D == 64)
-    k_stats<64><<<grid, 256, 0, st>>>(q_win, d.dtype, w, d.rope_layout, d.ddof, tab, mu, sigma);
-  else if (d.D == 128)
-    k_stats<128><<<grid, 256, 0, st>>>(q_win, d.dtype, w, d.rope_layout, d.ddof, tab, mu, sigma);
-  else
-    k_stats<256><<<grid, 256, 0, st>>>(q_win, d.dtype, w, d.rope_layout, d.ddof, tab, mu, sigma);
-  return hipGetLastError();
+  const bool bf = d.dtype == EA_BF16;
+  if (d.D == 64) return bf ? launch_stats_one<64, true>(d, q_win, w, tab, mu, sigma, st)
+                           : launch_stats_one<64, false>(d, q_win, w, tab, mu, sigma, st);
+  if (d.D == 128) return bf ? launch_stats_one<128, true>(d, q_win, w, tab, mu, sigma, st)
+                            : launch_stats_one<128, false>(d, q_win, w, tab, mu, sigma, st);
+  return bf ? launch_stats_one<256, true>(d, q_win, w, tab, mu, sigma, st)
+            : launch_stats_one<256, false>(d, q_win, w, tab, mu, sigma, st);
 }
 
 hipError_t launch_prep_frags(const Dims& d, const ScorePlan& sp, const float* mu,
