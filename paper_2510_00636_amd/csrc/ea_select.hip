@@ -27,43 +27,51 @@ hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st) {
 }
 
 // Bin b (counting down from the top) with  count(bins > b) < target <= count(bins >= b);
-// *rem = target - count(bins > b).  All 256 threads call it; result is uniform.
-// hist has nbins (multiple of 256, <= 2048) entries; s_tmp holds 257 words.
-__device__ int find_bin(const uint32_t* __restrict__ hist, int nbins, uint32_t target,
-                        uint32_t* rem, uint32_t* s_tmp) {
-  const int tid = threadIdx.x;
-  const int per = nbins / kSelThreads;
-  // thread t owns bins [nbins - per*(t+1), nbins - per*t): descending order across threads
-  const int hi = nbins - per * tid;
-  uint32_t loc[8];
+// *rem = target - count(bins > b).  Called by all 64 lanes of ONE wavefront; the result is
+// uniform.  nbins is 2048 or 1024; lane l owns the nbins/64 bins just below nbins - l*nbins/64.
+__device__ int find_bin_wave(const uint32_t* __restrict__ hist, int nbins, uint32_t target,
+                             uint32_t* rem, int lane) {
+  const int per = nbins / 64;                        // 32 or 16
+  const int lo = nbins - per * (lane + 1);
+  uint32_t loc[32];
   uint32_t sum = 0;
-  for (int j = 0; j < per; ++j) { loc[j] = hist[hi - 1 - j]; sum += loc[j]; }
-  __syncthreads();
-  s_tmp[tid] = sum;
-  __syncthreads();
-  // inclusive scan over threads (Hillis-Steele)
-  for (int o = 1; o < kSelThreads; o <<= 1) {
-    uint32_t add = tid >= o ? s_tmp[tid - o] : 0;
-    __syncthreads();
-    s_tmp[tid] += add;
-    __syncthreads();
-  }
-  const uint32_t incl = s_tmp[tid], excl = incl - sum;
-  if (excl < target && target <= incl) {
-    uint32_t cum = excl;
-    int b = hi - 1;
-    for (int j = 0; j < per; ++j) {
-      if (target <= cum + loc[j]) { b = hi - 1 - j; break; }
-      cum += loc[j];
+  const uint4* hp = reinterpret_cast<const uint4*>(hist + lo);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if (4 * j < per) {
+      const uint4 v = hp[j];
+      loc[4 * j] = v.x; loc[4 * j + 1] = v.y; loc[4 * j + 2] = v.z; loc[4 * j + 3] = v.w;
+      sum += v.x + v.y + v.z + v.w;
+    } else {
+      loc[4 * j] = loc[4 * j + 1] = loc[4 * j + 2] = loc[4 * j + 3] = 0;
     }
-    s_tmp[256] = (uint32_t)b;
-    s_tmp[257] = target - cum;
   }
-  __syncthreads();
-  const int b = (int)s_tmp[256];
-  *rem = s_tmp[257];
-  __syncthreads();
-  return b;
+  uint32_t incl = sum;                               // inclusive scan over lanes (lane 0 = top bins)
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  const uint32_t excl = incl - sum;
+  const bool mine = excl < target && target <= incl;
+  int b = 0;
+  uint32_t r = 0;
+  if (mine) {
+    uint32_t cum = excl;
+    b = lo;
+    r = target - cum;
+#pragma unroll
+    for (int j = 31; j >= 0; --j) {                  // walk this lane's bins from the top down
+      if (j < per) {
+        if (target > cum && target <= cum + loc[j]) { b = lo + j; r = target - cum; }
+        cum += loc[j];
+      }
+    }
+  }
+  const unsigned long long m = __ballot(mine);
+  const int src = m ? __ffsll((long long)m) - 1 : 0;
+  *rem = __shfl(r, src);
+  return __shfl(b, src);
 }
 
 struct SelArgs {
@@ -76,16 +84,24 @@ struct SelArgs {
   int nblk;
 };
 
-// Digits already fixed before pass P; returns true prefix for matching and the remaining rank.
+// Digits fixed by the histogram passes before pass P: wavefront 0 re-derives them (a few
+// hundred cycles, cheaper than another launch) and the workgroup reads them from s_res.
 template <int P>
-__device__ void resolve(const SelArgs& a, int unit, uint32_t* s_tmp, uint32_t* prefix, uint32_t* rem) {
-  const uint32_t* h = a.hist + (size_t)unit * 3 * kSelBins;
-  uint32_t r = a.n_keep, pre = 0;
-  if (P >= 1) { int b0 = find_bin(h, 2048, r, &r, s_tmp); pre = (uint32_t)b0; }
-  if (P >= 2) { int b1 = find_bin(h + kSelBins, 2048, r, &r, s_tmp); pre = (pre << 11) | (uint32_t)b1; }
-  if (P >= 3) { int b2 = find_bin(h + 2 * kSelBins, 1024, r, &r, s_tmp); pre = (pre << 10) | (uint32_t)b2; }
-  *prefix = pre;
-  *rem = r;
+__device__ void resolve(const SelArgs& a, int unit, uint32_t* s_res, uint32_t* prefix, uint32_t* rem) {
+  if (P >= 1 && threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    const uint32_t* h = a.hist + (size_t)unit * 3 * kSelBins;
+    uint32_t r = a.n_keep, pre = 0;
+    const int b0 = find_bin_wave(h, 2048, r, &r, lane);
+    pre = (uint32_t)b0;
+    if (P >= 2) { const int b1 = find_bin_wave(h + kSelBins, 2048, r, &r, lane); pre = (pre << 11) | (uint32_t)b1; }
+    if (P >= 3) { const int b2 = find_bin_wave(h + 2 * kSelBins, 1024, r, &r, lane); pre = (pre << 10) | (uint32_t)b2; }
+    if (lane == 0) { s_res[0] = pre; s_res[1] = r; }
+  }
+  __syncthreads();
+  *prefix = P >= 1 ? s_res[0] : 0u;
+  *rem = P >= 1 ? s_res[1] : a.n_keep;
+  __syncthreads();
 }
 
 template <int P>
@@ -174,18 +190,29 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_emit(SelArgs a) {
   const int tid = threadIdx.x, unit = blockIdx.x, blk = blockIdx.y;
   const uint32_t* slot = a.hist + ((size_t)unit * 3 + 2) * kSelBins + 1024;
   const uint32_t T = slot[0], q = slot[1];
-  if (tid == 0) {
-    // kept pairs and ==T pairs in the blocks before this one
-    uint32_t kept = 0, eqs = 0;
+  if (tid < 64) {
+    // kept pairs and ==T pairs in the blocks before this one: the lanes of wavefront 0 take the
+    // earlier blocks in order (64 at a time) and scan them
     const uint32_t* b = a.blk + (size_t)unit * a.nblk * 2;
-    for (int j = 0; j < blk; ++j) {
-      const uint32_t g = b[2 * j], e = b[2 * j + 1];
-      const uint32_t room = q > eqs ? q - eqs : 0;
-      kept += g + (e < room ? e : room);
-      eqs += e;
+    uint32_t kept = 0, eqs = 0;                     // totals of all earlier blocks seen so far
+    for (int j0 = 0; j0 < blk; j0 += 64) {
+      const int j = j0 + tid;
+      const uint32_t g = j < blk ? b[2 * j] : 0u, e = j < blk ? b[2 * j + 1] : 0u;
+      uint32_t ei = e;                              // inclusive scan of e over the lanes
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(ei, o);
+        if (tid >= o) ei += up;
+      }
+      const uint32_t eq_before = eqs + ei - e;      // ==T pairs before block j
+      const uint32_t room = q > eq_before ? q - eq_before : 0u;
+      uint32_t k = g + (e < room ? e : room);       // kept pairs of block j
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) k += __shfl_xor(k, o);
+      kept += k;
+      eqs += __shfl(ei, 63);
     }
-    s_base[0] = kept;
-    s_base[1] = eqs;
+    if (tid == 0) { s_base[0] = kept; s_base[1] = eqs; }
   }
   __syncthreads();
   const uint32_t base_kept = s_base[0], base_eq = s_base[1];
