@@ -11,7 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.environ.get("EA_CSRC") or os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libea.so")
-SOURCES = ["ea_host.cpp", "ea_api.hip", "ea_stats.hip", "ea_score.hip", "ea_select.hip",
+SOURCES = ["ea_host.cpp", "ea_api.hip", "ea_stats.hip", "ea_score.hip", "ea_score_d64.hip", "ea_score_d128.hip", "ea_score_d128b.hip",
+           "ea_score_d256.hip", "ea_select.hip",
            "ea_compact.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for the device pass (the host pass warns that it
@@ -37,7 +38,7 @@ def build_lib(verbose=True, extra_flags=(), out=None):
         LIB = out or LIB
         OBJ = os.path.join(OBJ, "variant_" + os.path.basename(LIB))
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 2)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 2)) as ex:
         res = list(ex.map(_compile, SOURCES))
     objs = [o for o, _ in res]
     if verbose:

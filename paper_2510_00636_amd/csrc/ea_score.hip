@@ -6,416 +6,9 @@
 //           (max, sum exp) pair per query head.
 //   pass B  k_finalize : combine the pairs into log-sum-exp per head, then
 //           score = (mean_g exp(l_g - lse_g) + eps) * ||v||.
-#include <hip/hip_runtime.h>
+#include "ea_score_mfma.h"
 
-#include <type_traits>
-
-#include "ea_kernels.h"
-
-#ifndef EA_FRAG_PREFETCH
-#define EA_FRAG_PREFETCH 4        // LDS fragments in flight ahead of the MFMA that consumes them
-#endif
 namespace ea {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-// native 16-byte vector: plain loads/stores the optimiser can keep in registers (HIP's uint4 is
-// a struct whose copies go through memcpy)
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-struct ScoreArgs {
-  const u32x4* k;
-  const u32x4* v;
-  long long n, n_cap;
-  const u32x4* frags;
-  const float* post;
-  float* logits;
-  float* vnorm;
-  float2* part;
-  int G, passes, span, nchunk, units, nfrag;
-};
-
-__device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
-  // bf16 -> fp32 is a 16-bit shift; fp32 -> fp16 is exact for |x| in [2^-14, 65504]
-  // (a bf16 significand has 8 bits, fp16 keeps 11), so round-toward-zero loses nothing there.
-  auto cv = [](uint32_t w) {
-    return __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
-  };
-  auto a = cv(r[0]), b = cv(r[1]), c = cv(r[2]), d = cv(r[3]);
-  half8 o;
-  o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
-  o[4] = c[0]; o[5] = c[1]; o[6] = d[0]; o[7] = d[1];
-  return o;
-}
-
-__device__ __forceinline__ float sumsq_bf16x8(u32x4 r) {
-  // plain scalar copies first: __builtin_bit_cast applied directly to a vector-element
-  // expression (r.y ...) reads element 0 of the vector
-  const uint32_t w0 = r[0], w1 = r[1], w2 = r[2], w3 = r[3];
-  const bf16x2 a = __builtin_bit_cast(bf16x2, w0), b = __builtin_bit_cast(bf16x2, w1);
-  const bf16x2 c = __builtin_bit_cast(bf16x2, w2), d = __builtin_bit_cast(bf16x2, w3);
-  float s = 0.f;
-  s = __builtin_amdgcn_fdot2_f32_bf16(a, a, s, false);
-  s = __builtin_amdgcn_fdot2_f32_bf16(b, b, s, false);
-  s = __builtin_amdgcn_fdot2_f32_bf16(c, c, s, false);
-  s = __builtin_amdgcn_fdot2_f32_bf16(d, d, s, false);
-  return s;
-}
-
-// x + (x of another lane of the same 16-lane row), selected by a DPP control word
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
-  return x + __int_as_float(y);
-}
-
-// Sum over aligned groups of N consecutive lanes (N = 8, 16 or 32); every lane gets the total.
-template <int N>
-__device__ __forceinline__ float group_sum(float x) {
-  x = dpp_add<0xB1>(x);                       // quad_perm [1,0,3,2]
-  x = dpp_add<0x4E>(x);                       // quad_perm [2,3,0,1]
-  x = dpp_add<0x141>(x);                      // row_half_mirror: lanes 0-7 <-> 7-0 of each half row
-  if (N >= 16) x = dpp_add<0x140>(x);         // row_mirror
-  if (N >= 32) x += __shfl_xor(x, 16);
-  return x;
-}
-
-// merge two online-softmax states (m, s): value = s * exp(m)
-__device__ __forceinline__ void merge_ms(float& m, float& s, float m2, float s2) {
-  float mn = fmaxf(m, m2);
-  if (mn == -INFINITY) { s = 0.f; m = mn; return; }
-  s = s * __expf(m - mn) + s2 * __expf(m2 - mn);
-  m = mn;
-}
-
-// compile-time loop: f(std::integral_constant<int, 0>) ... f(<N-1>), so that every register
-// array index below is a constant
-template <int N, int I = 0, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<N, I + 1>(f);
-  }
-}
-
-// output tile index jt of the rem-th fragment of a head (tile jt owns fragments
-// jt*(jt+1) .. jt*(jt+1) + 2jt + 1 of the triangular tiling)
-constexpr int tri_jt(int rem) {
-  int jt = 0;
-  while (rem >= (jt + 1) * (jt + 2)) ++jt;
-  return jt;
-}
-// LDS fragment index used by matrix-core step f (the extra tile's fragments are stored last)
-template <int GH, int NF, int NX>
-constexpr int step_frag(int f) { return f < NX ? GH * NF + f : f - NX; }
-
-// The 2*NL global loads of the next tile are spread evenly over the steps [NX, NS).
-template <int NX, int NS, int NL>
-constexpr int load_slot(int i) { return NX + (i * (NS - NX)) / (2 * NL); }
-// accumulator row rho of a 32x32 tile lives in register ROW_V(rho) of the lanes with
-// lane / 32 == ROW_HH(rho)  (column = lane % 32)
-#define ROW_V(rho) (4 * ((rho) / 8) + (rho) % 4)
-#define ROW_HH(rho) (((rho) / 4) % 2)
-
-// ---------------------------------------------------------------------------------------
-// One wavefront scores 32 keys per iteration.  Lane l = (r = l % 32, hh = l / 32) owns the
-// channels hh*d/2 .. hh*d/2 + d/2 - 1 of key r as fp16 (B operand of the 32x32x16 MFMA), the
-// fragments of M (A operand) come from LDS, and the accumulator layout hands the lane the
-// same channels back, so  sum_j acc_j k_j  is 16 mixed-precision FMAs per output tile.
-// K rows reach that layout through a per-wave LDS staging buffer (coalesced 16-byte global
-// loads in, conflict-free 16-byte LDS reads out); V rows are squared and summed straight
-// from the coalesced layout.  The next tile's K and V loads are issued before the matrix
-// work of the current one.
-//
-// Ragged tail: the last tile of a head is moved back to start at n - 32, so it overlaps its
-// predecessor instead of running past the tensor; the keys it shares with the predecessor are
-// recomputed and masked out of the stores and of the softmax sums.  Heads shorter than one tile
-// (n < 32) use the CLAMP instance, which clamps every row index instead.
-template <int D, int GH, int NW, bool CLAMP>
-__global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
-  constexpr int NKS = D / 16, NJT = D / 32, NF = NJT * (NJT + 1);
-  constexpr int NFRAG = GH * NF + 2 * NKS;
-  constexpr int CPR = D / 8;            // 16-byte chunks per row
-  constexpr int RPL = 64 / CPR;         // rows per wave-wide load
-  constexpr int NL = 32 / RPL;          // wave-wide loads per 32-key tile
-  constexpr int NKH = NKS / 2;          // k-steps staged per phase
-  constexpr int RP = CPR / 2;           // staged chunks per row and phase
-  constexpr int RPS = 16 / RP;          // staged rows per 256 bytes (one sweep of the LDS banks)
-  extern __shared__ u32x4 smem[];
-  const half8* fr = reinterpret_cast<const half8*>(smem);
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: lives in an SGPR
-  u32x4* stg = smem + NFRAG * 64 + wave * (16 * CPR);
-  float2* red = reinterpret_cast<float2*>(smem + NFRAG * 64 + NW * (16 * CPR));
-
-  const int bid = blockIdx.x;
-  const int unit = bid % a.units;
-  const int t2 = bid / a.units;
-  const int chunk = t2 % a.nchunk, pass = t2 / a.nchunk;
-  const int g0 = pass * GH;
-  const bool do_v = pass == 0;
-
-  {  // fragments of this (unit, pass) -> LDS
-    const u32x4* src = a.frags + ((size_t)unit * a.passes + pass) * NFRAG * 64;
-#pragma unroll
-    for (int it = 0; it < (NFRAG + NW - 1) / NW; ++it) {
-      const int i = tid + it * NW * 64;
-      if (i < NFRAG * 64) smem[i] = src[i];
-    }
-  }
-  float pq[GH], pm[GH];
-#pragma unroll
-  for (int g = 0; g < GH; ++g) {
-    const bool ok = g0 + g < a.G;
-    pq[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 0] : 0.f;
-    pm[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 1] : 0.f;
-  }
-  __syncthreads();
-
-  const int r = lane & 31, hh = lane >> 5;
-  const int lrow = lane / CPR, lch = lane % CPR;
-  // Workgroup `chunk` of a unit takes the 32*NW-key blocks chunk, chunk + nchunk, ... : at any
-  // moment the workgroups of a unit stream one contiguous region, which spreads the traffic
-  // over all HBM channels (contiguous per-workgroup spans would march through memory in
-  // lock step at a fixed large stride and pile onto a few channels).
-  const long long key_stride = (long long)a.nchunk * (NW * 32);
-  const long long key_hi = a.n;
-  const u32x4* kbase = a.k + (size_t)unit * a.n_cap * CPR;
-  const u32x4* vbase = a.v + (size_t)unit * a.n_cap * CPR;
-
-  float m_run[GH], s_run[GH];
-#pragma unroll
-  for (int g = 0; g < GH; ++g) { m_run[g] = -INFINITY; s_run[g] = 0.f; }
-
-  // One 32-key tile = NL wave-wide 16-byte loads per tensor, addressed as (uniform tile base)
-  // + lane*16 + j*1024 so that the address arithmetic stays on the scalar unit.
-  u32x4 kraw[NL], vraw[NL];
-  auto tile_base = [&](long long k0) -> long long {          // first row actually loaded
-    return (!CLAMP && k0 + 32 > a.n) ? a.n - 32 : k0;
-  };
-#pragma unroll
-  for (int j = 0; j < NL; ++j) { kraw[j] = u32x4{0u, 0u, 0u, 0u}; vraw[j] = u32x4{0u, 0u, 0u, 0u}; }
-  long long key0 = ((long long)chunk * NW + wave) * 32;
-  if (key0 < key_hi) {                                       // first tile: plain loads
-    if constexpr (!CLAMP) {
-      const u32x4* kp = kbase + tile_base(key0) * CPR;
-      const u32x4* vp = vbase + tile_base(key0) * CPR;
-#pragma unroll
-      for (int j = 0; j < NL; ++j) kraw[j] = kp[j * 64 + lane];
-      if (do_v) {
-#pragma unroll
-        for (int j = 0; j < NL; ++j) vraw[j] = vp[j * 64 + lane];
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < NL; ++j) {
-        const long long row = min(key0 + j * RPL + lrow, a.n - 1);
-        kraw[j] = kbase[row * CPR + lch];
-        if (do_v) vraw[j] = vbase[row * CPR + lch];
-      }
-    }
-  }
-
-  // Results of a tile are stored one iteration later, right after the staging of the next
-  // tile: global stores share the in-order counter of the loads, and stores issued while
-  // loads are pending make every later wait for a load also wait for the store.
-  float lg_prev[GH], vsq_prev = 0.f;
-#pragma unroll
-  for (int g = 0; g < GH; ++g) lg_prev[g] = 0.f;
-  long long key_prev = 0;
-  bool have_prev = false;
-  auto store_prev = [&]() {
-    const long long b0 = tile_base(key_prev);
-    const long long key = b0 + r;
-    if (hh == 0 && key >= key_prev && key < a.n) {
-#pragma unroll
-      for (int g = 0; g < GH; ++g)
-        if (g0 + g < a.G) a.logits[((size_t)unit * a.G + g0 + g) * a.n + key] = lg_prev[g];
-    }
-    if (do_v) {
-      const long long row = b0 + lch * RPL + lrow;
-      if (lch < NL && row >= key_prev && row < a.n)
-        a.vnorm[(size_t)unit * a.n + row] = __builtin_amdgcn_sqrtf(vsq_prev);
-    }
-  };
-
-  for (; key0 < key_hi; key0 += key_stride) {
-    // ---- K: coalesced registers -> LDS -> MFMA B layout.  Two phases, each staging one half
-    //      of every lane's k-steps for all 32 rows (half-size buffer, all lanes busy).
-    half8 Kh[NKS];
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-      if (((lch % NKS) / NKH) == hf) {
-        const int sc = (lch / NKS) * NKH + (lch % NKH);
-#pragma unroll
-        for (int j = 0; j < NL; ++j) {
-          const int rho = j * RPL + lrow;
-          stg[rho * RP + (sc ^ ((rho / RPS) & (RP - 1)))] = kraw[j];
-        }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int q = 0; q < NKH; ++q) {
-        const int sc = hh * NKH + q;
-        Kh[hf * NKH + q] = bf16x8_to_half8(stg[r * RP + (sc ^ ((r / RPS) & (RP - 1)))]);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    }
-    if (have_prev) store_prev();
-
-    // ---- where the next tile comes from.  Without a next tile the loads below still run (the
-    //      matrix-core phase is one straight-line block) but all lanes read the head's first
-    //      16 bytes: no traffic to speak of.
-    const long long nkey0 = key0 + key_stride;
-    const bool has_next = nkey0 < key_hi;
-    const u32x4* kp_n = has_next ? kbase + tile_base(nkey0) * CPR : kbase;
-    const u32x4* vp_n = (has_next && do_v) ? vbase + tile_base(nkey0) * CPR : vbase;
-    const int kl = has_next ? lane : 0, vl = (has_next && do_v) ? lane : 0;
-    const int kj = has_next ? 64 : 0, vj = (has_next && do_v) ? 64 : 0;
-
-    // ---- matrix-core phase: NS = 2*NKS + GH*NF steps, one LDS fragment and one MFMA each.
-    //   steps [0, NKS)       extra tile, rows g / GH+g = fp16 head / tail of mu, times k
-    //   steps [NKS, 2NKS)    extra tile, rows 2GH+g = rounding residual of diag(M), times k^2/256
-    //   then per output tile t = (head g, 32 output channels jt): 2jt+2 steps over the k-steps on
-    //   or below the diagonal; its accumulator is then dotted with k (16 FMAs).
-    // Everything else of the iteration rides in the shadow of the MFMAs:
-    //   * fragments are fetched PD steps ahead into a register ring;
-    //   * the 16 FMAs of tile t are issued four per step during steps end(t)+2 .. end(t)+5
-    //     (three accumulators rotate, so a tile is not rewritten before it has been read);
-    //   * the squared norm of V chunk j is formed at step j;
-    //   * the 2*NL global loads of the next tile are spread over the steps after the extra
-    //     tile, one at a time, so they never queue up in front of the memory pipeline.
-    float lin[GH], partial[GH], vsq = 0.f;
-    static_for<GH>([&](auto g_) { partial[decltype(g_)::value] = 0.f; lin[decltype(g_)::value] = 0.f; });
-    {
-      constexpr int NX = 2 * NKS, NS = NX + GH * NF, NT = GH * NJT, PD = EA_FRAG_PREFETCH;
-      half8 fb[PD + 1];
-      floatx16 ex, accb[3];
-      static_for<PD>([&](auto i_) {
-        constexpr int i = decltype(i_)::value;
-        fb[i] = fr[step_frag<GH, NF, NX>(i) * 64 + lane];
-      });
-      __builtin_amdgcn_sched_barrier(0);
-      // FMAs 4q .. 4q+3 of the dot product of tile tt
-      auto dot4 = [&](auto tt_, auto q_) {
-        constexpr int tt = decltype(tt_)::value, q = decltype(q_)::value;
-        constexpr int g = tt / NJT, jt = tt % NJT;
-        static_for<4>([&](auto v_) {
-          constexpr int v = 4 * q + decltype(v_)::value;
-          constexpr int x = jt * 16 + v;
-          partial[g] = fmaf(accb[tt % 3][v], (float)Kh[x / 8][x % 8], partial[g]);
-        });
-        // pin: otherwise the optimiser sinks the dot products to the end of the phase and keeps
-        // every accumulator tile alive
-        if constexpr (q == 3) asm volatile("" : "+v"(partial[g]));
-      };
-      static_for<NS + 6>([&](auto f_) {
-        constexpr int f = decltype(f_)::value;
-        if constexpr (f < NS) {
-          if constexpr (f + PD < NS)
-            fb[(f + PD) % (PD + 1)] = fr[step_frag<GH, NF, NX>(f + PD) * 64 + lane];
-          const half8 A = fb[f % (PD + 1)];
-          constexpr floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          if constexpr (f < NKS) {
-            ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Kh[f], f == 0 ? zero : ex, 0, 0, 0);
-          } else if constexpr (f < NX) {
-            half8 t = Kh[f - NKS] * (_Float16)0.0625f;
-            t = t * t;
-            ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, t, ex, 0, 0, 0);
-          } else {
-            constexpr int m = f - NX, g = m / NF, rem = m % NF;
-            constexpr int jt = tri_jt(rem), kt = rem - jt * (jt + 1), t = g * NJT + jt;
-            accb[t % 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Kh[kt], kt == 0 ? zero : accb[t % 3], 0, 0, 0);
-          }
-        }
-        // ---- vector work placed in this step
-        if constexpr (f < NL) {                   // V chunk f: lane lch == f keeps its row's sum
-          const float ss = group_sum<CPR>(sumsq_bf16x8(vraw[f]));
-          vsq = lch == f ? ss : vsq;
-        }
-        if constexpr (f == NX + 1) {              // rows of the extra tile, two steps after its end
-          static_for<GH>([&](auto g_) {
-            constexpr int g = decltype(g_)::value;
-            float e = 0.f;
-            if (hh == ROW_HH(g)) e += ex[ROW_V(g)] * pm[g];
-            if (hh == ROW_HH(GH + g)) e += ex[ROW_V(GH + g)] * pm[g];
-            if (hh == ROW_HH(2 * GH + g)) e += ex[ROW_V(2 * GH + g)] * (256.0f * pq[g]);
-            lin[g] = e;
-          });
-        }
-        static_for<NT>([&](auto tt_) {
-          constexpr int tt = decltype(tt_)::value;
-          constexpr int e = NX + (tt / NJT) * NF + (tt % NJT + 1) * (tt % NJT + 2) - 1;   // last step of tile tt
-          if constexpr (f >= e + 2 && f < e + 6) dot4(tt_, std::integral_constant<int, f - e - 2>{});
-        });
-        // ---- loads of the next tile that belong to this step (K first, then V)
-        static_for<2 * NL>([&](auto i_) {
-          constexpr int i = decltype(i_)::value;
-          if constexpr (f < NS && load_slot<NX, NS, NL>(i) == f) {
-            if constexpr (i < NL) kraw[i] = kp_n[i * kj + kl];
-            else vraw[i - NL] = vp_n[(i - NL) * vj + vl];
-          }
-        });
-        // Nothing may move across a step: the program order written above -- fragment read PD
-        // steps ahead, one MFMA, the vector / memory work that rides in its shadow -- is the
-        // software pipeline.  (Left alone, the scheduler sinks every LDS read next to its MFMA.)
-        __builtin_amdgcn_sched_barrier(0);
-      });
-    }
-    const bool valid = tile_base(key0) + r >= key0 && tile_base(key0) + r < a.n;
-#pragma unroll
-    for (int g = 0; g < GH; ++g) {
-      float lg = partial[g] * pq[g] + lin[g];
-      lg += __shfl_xor(lg, 32);
-      lg_prev[g] = lg;
-      if (valid && g0 + g < a.G) {
-        float mn = fmaxf(m_run[g], lg);
-        s_run[g] = s_run[g] * __expf(m_run[g] - mn) + __expf(lg - mn);
-        m_run[g] = mn;
-      }
-    }
-    vsq_prev = vsq;
-    key_prev = key0;
-    have_prev = true;
-  }
-  if (have_prev) store_prev();
-
-  // ---- (max, sum) of this workgroup's keys, per head
-#pragma unroll
-  for (int g = 0; g < GH; ++g) {
-    float m = m_run[g], s = s_run[g];
-#pragma unroll
-    for (int o = 16; o >= 1; o >>= 1) {
-      float m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
-      merge_ms(m, s, m2, s2);
-    }
-    if (lane == 0) red[wave * GH + g] = make_float2(m, s);
-  }
-  __syncthreads();
-  if (tid < GH && g0 + tid < a.G) {
-    float m = -INFINITY, s = 0.f;
-    for (int w = 0; w < NW; ++w) {
-      float2 o = red[w * GH + tid];
-      merge_ms(m, s, o.x, o.y);
-    }
-    a.part[((size_t)unit * a.G + g0 + tid) * a.nchunk + chunk] = make_float2(m, s);
-  }
-}
-
-template <int D, int GH, int NW, bool CLAMP>
-static hipError_t launch_one(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st) {
-  auto kern = k_score_mfma<D, GH, NW, CLAMP>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp.lds_bytes);
-  if (e != hipSuccess) return e;
-  int grid = a.units * a.nchunk * a.passes;
-  kern<<<grid, NW * 64, sp.lds_bytes, st>>>(a);
-  return hipGetLastError();
-}
 
 hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
@@ -436,20 +29,11 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
   a.nchunk = sp.nchunk;
   a.units = d.units();
   a.nfrag = sp.nfrag;
-#define EA_CASE(DD, GG, WW)                                                         \
-  if (d.D == DD && sp.GH == GG && sp.NW == WW)                                      \
-  return n < 32 ? launch_one<DD, GG, WW, true>(a, sp, st) : launch_one<DD, GG, WW, false>(a, sp, st)
-  EA_CASE(64, 1, 8);
-  EA_CASE(64, 2, 8);
-  EA_CASE(64, 4, 8);
-  EA_CASE(64, 8, 8);
-  EA_CASE(128, 1, EA_NW128);
-  EA_CASE(128, 2, EA_NW128);
-  EA_CASE(128, 3, EA_NW128);
-  EA_CASE(128, 4, EA_NW128);
-  EA_CASE(128, 5, EA_NW128);
-  EA_CASE(256, 1, 4);
-#undef EA_CASE
+  switch (d.D) {
+    case 64: return launch_score_mfma_d64(a, sp, st);
+    case 128: return sp.GH <= 3 ? launch_score_mfma_d128(a, sp, st) : launch_score_mfma_d128b(a, sp, st);
+    case 256: return launch_score_mfma_d256(a, sp, st);
+  }
   return hipErrorInvalidValue;
 }
 
