@@ -37,6 +37,10 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--epsilon", type=float, default=0.02)
+    ap.add_argument("--streams", type=int, default=3,
+                    help="HIP streams the layers are spread over (each with its own workspace); layers "
+                         "are independent, so the short latency-bound kernels of one layer overlap "
+                         "with the streaming kernels of another")
     return ap.parse_args()
 
 
@@ -85,7 +89,10 @@ def main():
         lay = make_layer_device(cfg, l, out_k=k0[l], out_v=v0[l], out_q=q[l])
         inv = lay["inv_freq"]
     k, v = torch.empty_like(k0), torch.empty_like(v0)
-    ws = torch.empty(ea.workspace_bytes(p, n, w), dtype=torch.uint8, device=dev)
+    ns = max(1, min(a.streams, L))
+    wss = [torch.empty(ea.workspace_bytes(p, n, w), dtype=torch.uint8, device=dev) for _ in range(ns)]
+    ws = wss[0]
+    streams = [torch.cuda.Stream() for _ in range(ns)] if ns > 1 else [None]      # default priority
     q_pos0, t_next = n - w, n
     torch.cuda.synchronize()
 
@@ -94,13 +101,17 @@ def main():
         v.copy_(v0)
 
     def step():
+        # layer l runs on stream l % ns with that stream's workspace; the caller synchronises
+        # the device before and after a step
         for l in range(L):
-            ea.compress_layer(p, q[l], w, q_pos0, inv, t_next, k[l], v[l], n, n, n_keep, None, None, ws)
+            ea.compress_layer(p, q[l], w, q_pos0, inv, t_next, k[l], v[l], n, n, n_keep, None, None,
+                              wss[l % ns], stream=streams[l % ns])
 
     for _ in range(a.warmup):
         restore()
+        torch.cuda.synchronize()
         step()
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
     times = []
     for _ in range(a.steps):
         restore()
@@ -146,8 +157,8 @@ def main():
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
            "config": {"workload": "%s: %d layers x %d KV heads x %d tokens x d%d, Hq %d, window %d, "
-                                  "ratio %.2f (keep %d), eps %.2f, in place" %
-                                  (cfg.name, L, Hkv * B, n, d, Hq, w, a.ratio, n_keep, a.epsilon),
+                                  "ratio %.2f (keep %d), eps %.2f, in place, layers spread over %d streams" %
+                                  (cfg.name, L, Hkv * B, n, d, Hq, w, a.ratio, n_keep, a.epsilon, ns),
                       "pairs_per_step": pairs, "bytes_per_pair": bytes_per_pair},
            "path_hbm_frac": round(path_hbm_frac, 4),
            "stage_ms_per_layer": stages,

@@ -10,6 +10,7 @@ import pytest
 from ea_inputs import CONFIGS, make_layer, widen
 from oracle import ea_oracle as O
 from tests import parity as P
+import paper_2510_00636_amd as ea
 
 pytestmark = pytest.mark.gpu
 
@@ -243,3 +244,36 @@ def test_compress_layer_c2_full_size():
                                lay["inv_freq"], lay["t_next"], n_keep, T=cfg.horizon_T, epsilon=eps,
                                k_store=lay["k"], v_store=lay["v"])
         P.check_layer(cfg, lay, got, ref, n_keep, 2e-3)
+
+
+def test_layers_on_concurrent_streams_match_sequential():
+    """Layers are independent: compressing them on several streams, each with its own workspace
+    (the launch configuration bench.py times), gives the bytes the one-stream order gives."""
+    import torch
+    cfg = CONFIGS["c2"].with_(n_q_heads=8, n_kv_heads=2)
+    n, w, n_keep, L = 6000, 64, 3000, 6
+    lays = [make_layer(cfg, layer=l, n=n, window=w) for l in range(L)]
+    seq = [P.run_compress_layer(cfg, lay, n_keep) for lay in lays]
+    p = P.params_for(cfg)
+    ns = 3
+    streams = [torch.cuda.Stream() for _ in range(ns)]
+    wss = [P.workspace(p, n, w) for _ in range(ns)]
+    dev = [dict(q=P.to_dev(lay["q_win"]), k=P.to_dev(lay["k"]), v=P.to_dev(lay["v"]),
+                f=P.to_dev(lay["inv_freq"])) for lay in lays]
+    idx = [torch.full((cfg.batch, cfg.n_kv_heads, n_keep), -1, dtype=torch.int32, device="cuda")
+           for _ in range(L)]
+    torch.cuda.synchronize()
+    for rep in range(2):                            # second round: workspaces are reused dirty
+        if rep == 1:
+            for l, lay in enumerate(lays):
+                dev[l]["k"].copy_(P.to_dev(lay["k"]))
+                dev[l]["v"].copy_(P.to_dev(lay["v"]))
+            torch.cuda.synchronize()
+        for l, lay in enumerate(lays):
+            ea.compress_layer(p, dev[l]["q"], w, lay["q_pos0"], dev[l]["f"], lay["t_next"], dev[l]["k"],
+                              dev[l]["v"], n, n, n_keep, None, idx[l], wss[l % ns], stream=streams[l % ns])
+        torch.cuda.synchronize()
+        for l in range(L):
+            assert np.array_equal(idx[l].cpu().numpy(), seq[l]["idx"]), (rep, l)
+            assert np.array_equal(P.to_host(dev[l]["k"])[:, :, :n_keep], seq[l]["k"][:, :, :n_keep]), (rep, l)
+            assert np.array_equal(P.to_host(dev[l]["v"])[:, :, :n_keep], seq[l]["v"][:, :, :n_keep]), (rep, l)
