@@ -47,10 +47,17 @@ static ea_status run_stats(const Dims& d, const void* q_win, int64_t window, int
 
 // hist0 != nullptr: the finalize pass also fills the first radix-select histogram.
 // ev (nullable): ev[0] is recorded after the operand preparation, ev[1] after pass A.
+// The score kernel's tile counters live in words of the third histogram that the 1024-bin
+// last radix digit never touches; `hist_zeroed` says whether the caller's clearing launch has
+// covered them already.
+constexpr int kTicketSlot = 1040;
 static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                            const float* mu, const float* sigma, float* scores, uint32_t* hist0,
-                           char* ws, const WsLayout& L, hipStream_t st, hipEvent_t* ev = nullptr) {
+                           bool hist_zeroed, char* ws, const WsLayout& L, hipStream_t st,
+                           hipEvent_t* ev = nullptr) {
   float* vnorm = (float*)(ws + L.vnorm);
+  uint32_t* hist = (uint32_t*)(ws + L.hist);
+  if (d.dtype == EA_BF16 && !hist_zeroed) EA_TRY(launch_zero(hist, (size_t)d.units() * 3 * kSelBins, st));
   if (d.dtype == EA_BF16) {
     ScorePlan sp = make_score_plan(d, n, device_num_cu());
     uint4* frags = (uint4*)(ws + L.frags);
@@ -58,7 +65,8 @@ static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t 
     EA_TRY(launch_prep_frags(d, sp, mu, sigma, frags, post, st));
     if (ev) EA_TRY(hipEventRecord(ev[0], st));
     EA_TRY(launch_score_mfma(d, sp, k, v, n, n_cap, frags, post, (float*)(ws + L.logits), vnorm,
-                             (float2*)(ws + L.part), st));
+                             (float2*)(ws + L.part), hist + 2 * kSelBins + kTicketSlot, 3 * kSelBins,
+                             st));
     if (ev) EA_TRY(hipEventRecord(ev[1], st));
     EA_TRY(launch_finalize(d, n, ws + L.logits, 0, vnorm, ws + L.part, sp.nchunk, scores, hist0, st));
   } else {
@@ -111,7 +119,8 @@ ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, 
   if (n < 1 || n > n_cap || n > ((int64_t)1 << 30)) return EA_ERR_INVALID_ARG;
   WsLayout L;
   if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
-  return run_score(d, k, v, n, n_cap, mu, sigma, scores, nullptr, (char*)ws, L, (hipStream_t)stream);
+  return run_score(d, k, v, n, n_cap, mu, sigma, scores, nullptr, false, (char*)ws, L,
+                   (hipStream_t)stream);
 }
 
 ea_status ea_select(const ea_params* p, const float* scores, int64_t n, int64_t n_keep, int32_t* idx,
@@ -189,7 +198,7 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
                      clear_words)) != EA_OK)
     return s;
   if (ev) EA_TRY(hipEventRecord(ev[1], st));
-  if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores, n_keep > 0 ? hist : nullptr, w, L, st,
+  if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores, n_keep > 0 ? hist : nullptr, true, w, L, st,
                      ev ? ev + 2 : nullptr)) != EA_OK)
     return s;
   if (ev) EA_TRY(hipEventRecord(ev[4], st));

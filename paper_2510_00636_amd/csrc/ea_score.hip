@@ -12,7 +12,8 @@ namespace ea {
 
 hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
-                             float* logits, float* vnorm, float2* part, hipStream_t st) {
+                             float* logits, float* vnorm, float2* part, uint32_t* tickets,
+                             int ticket_stride, hipStream_t st) {
   ScoreArgs a;
   a.k = (const u32x4*)k;
   a.v = (const u32x4*)v;
@@ -29,6 +30,8 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
   a.nchunk = sp.nchunk;
   a.units = d.units();
   a.nfrag = sp.nfrag;
+  a.tickets = tickets;
+  a.ticket_stride = ticket_stride;
   switch (d.D) {
     case 64: return launch_score_mfma_d64(a, sp, st);
     case 128: return sp.GH <= 3 ? launch_score_mfma_d128(a, sp, st) : launch_score_mfma_d128b(a, sp, st);

@@ -33,6 +33,8 @@ struct ScoreArgs {
   float* vnorm;
   float2* part;
   int G, passes, span, nchunk, units, nfrag;
+  uint32_t* tickets;      // tickets + unit * ticket_stride + pass: tile counter, zero at launch
+  int ticket_stride;
 };
 
 __device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
@@ -148,7 +150,12 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   u32x4* stg = smem + NFRAG * 64 + wave * (16 * CPR);
   float2* red = reinterpret_cast<float2*>(smem + NFRAG * 64 + NW * (16 * CPR));
 
-  const int bid = blockIdx.x;
+  // Workgroups are dealt to the chip's 8 dies round-robin by index; the transposition below
+  // gives every unit workgroups on all of them.  Together with the tile tickets further down it
+  // lets the faster dies (clocks under matrix-core load differ by 15 % and more) take a larger
+  // share of a head instead of idling while the slowest one finishes.
+  int bid = blockIdx.x;
+  if ((gridDim.x & 7u) == 0) bid = (bid & 7) * (int)(gridDim.x >> 3) + (bid >> 3);
   const int unit = bid % a.units;
   const int t2 = bid / a.units;
   const int chunk = t2 % a.nchunk, pass = t2 / a.nchunk;
@@ -174,12 +181,20 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 
   const int r = lane & 31, hh = lane >> 5;
   const int lrow = lane / CPR, lch = lane % CPR;
-  // Workgroup `chunk` of a unit takes the 32*NW-key blocks chunk, chunk + nchunk, ... : at any
-  // moment the workgroups of a unit stream one contiguous region, which spreads the traffic
-  // over all HBM channels (contiguous per-workgroup spans would march through memory in
-  // lock step at a fixed large stride and pile onto a few channels).
-  const long long key_stride = (long long)a.nchunk * (NW * 32);
-  const long long key_hi = a.n;
+  // Tiles of 32 keys are handed out by a ticket counter per (unit, pass), last tile of the head
+  // first: at any moment the waves of a unit stream one contiguous region (which spreads the
+  // traffic over all HBM channels), and what the pass reads last, the early rows, is what the
+  // compaction that follows reads first, while it may still be in the memory-side cache.
+  // A wave holds two tickets ahead (the tile it prefetches and the one after), so the counter's
+  // round trip never shows.
+  const int ntiles = (int)((a.n + 31) / 32);
+  uint32_t* tk = a.tickets + (size_t)unit * a.ticket_stride + pass;
+  auto grab = [&]() -> int {               // valid in lane 0; v_readfirstlane where it is used
+    int t = 0;
+    if (lane == 0) t = (int)atomicAdd(tk, 1u);
+    return t;
+  };
+  auto tile_key = [&](int ticket) -> long long { return (long long)(ntiles - 1 - ticket) * 32; };
   const u32x4* kbase = a.k + (size_t)unit * a.n_cap * CPR;
   const u32x4* vbase = a.v + (size_t)unit * a.n_cap * CPR;
 
@@ -195,8 +210,10 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   };
 #pragma unroll
   for (int j = 0; j < NL; ++j) { kraw[j] = u32x4{0u, 0u, 0u, 0u}; vraw[j] = u32x4{0u, 0u, 0u, 0u}; }
-  long long key0 = ((long long)chunk * NW + wave) * 32;
-  if (key0 < key_hi) {                                       // first tile: plain loads
+  int t_cur = __builtin_amdgcn_readfirstlane(grab());
+  int t_nxt_raw = grab();
+  long long key0 = t_cur < ntiles ? tile_key(t_cur) : 0;
+  if (t_cur < ntiles) {                                      // first tile: plain loads
     if constexpr (!CLAMP) {
       const u32x4* kp = kbase + tile_base(key0) * CPR;
       const u32x4* vp = vbase + tile_base(key0) * CPR;
@@ -239,7 +256,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     }
   };
 
-  for (; key0 < key_hi; key0 += key_stride) {
+  for (; t_cur < ntiles; key0 = tile_key(t_cur)) {
     // ---- K: coalesced registers -> LDS -> MFMA B layout.  Two phases, each staging one half
     //      of every lane's k-steps for all 32 rows (half-size buffer, all lanes busy).
     half8 Kh[NKS];
@@ -268,8 +285,10 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     // ---- where the next tile comes from.  Without a next tile the loads below still run (the
     //      matrix-core phase is one straight-line block) but all lanes read the head's first
     //      16 bytes: no traffic to speak of.
-    const long long nkey0 = key0 + key_stride;
-    const bool has_next = nkey0 < key_hi;
+    const int t_nxt = __builtin_amdgcn_readfirstlane(t_nxt_raw);
+    t_nxt_raw = grab();
+    const bool has_next = t_nxt < ntiles;
+    const long long nkey0 = has_next ? tile_key(t_nxt) : 0;
     const u32x4* kp_n = has_next ? kbase + tile_base(nkey0) * CPR : kbase;
     const u32x4* vp_n = (has_next && do_v) ? vbase + tile_base(nkey0) * CPR : vbase;
     const int kl = has_next ? lane : 0, vl = (has_next && do_v) ? lane : 0;
@@ -379,6 +398,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     vsq_prev = vsq;
     key_prev = key0;
     have_prev = true;
+    t_cur = t_nxt;
   }
   if (have_prev) store_prev();
 
