@@ -162,12 +162,27 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   const int g0 = pass * GH;
   const bool do_v = pass == 0;
 
-  {  // fragments of this (unit, pass) -> LDS
+  // Prologue order: tile tickets, then the loads of this (unit, pass)'s fragments, then the
+  // first tile's K and V loads (they need the first ticket, which has had the fragment loads'
+  // issue time to come back), and only then the fragments' way into LDS and the barrier: the
+  // first tile travels while the workgroup assembles its fragments.
+  const int ntiles = (int)((a.n + 31) / 32);
+  uint32_t* tk = a.tickets + (size_t)unit * a.ticket_stride + pass;
+  auto grab = [&]() -> int {               // valid in lane 0; v_readfirstlane where it is used
+    int t = 0;
+    if (lane == 0) t = (int)atomicAdd(tk, 1u);
+    return t;
+  };
+  const int t_cur_raw = grab();
+  int t_nxt_raw = grab();
+  constexpr int NFIT = (NFRAG + NW - 1) / NW;
+  u32x4 ftmp[NFIT];
+  {
     const u32x4* src = a.frags + ((size_t)unit * a.passes + pass) * NFRAG * 64;
 #pragma unroll
-    for (int it = 0; it < (NFRAG + NW - 1) / NW; ++it) {
+    for (int it = 0; it < NFIT; ++it) {
       const int i = tid + it * NW * 64;
-      if (i < NFRAG * 64) smem[i] = src[i];
+      ftmp[it] = i < NFRAG * 64 ? src[i] : u32x4{0u, 0u, 0u, 0u};
     }
   }
   float pq[GH], pm[GH];
@@ -177,7 +192,6 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     pq[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 0] : 0.f;
     pm[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 1] : 0.f;
   }
-  __syncthreads();
 
   const int r = lane & 31, hh = lane >> 5;
   const int lrow = lane / CPR, lch = lane % CPR;
@@ -187,13 +201,6 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   // compaction that follows reads first, while it may still be in the memory-side cache.
   // A wave holds two tickets ahead (the tile it prefetches and the one after), so the counter's
   // round trip never shows.
-  const int ntiles = (int)((a.n + 31) / 32);
-  uint32_t* tk = a.tickets + (size_t)unit * a.ticket_stride + pass;
-  auto grab = [&]() -> int {               // valid in lane 0; v_readfirstlane where it is used
-    int t = 0;
-    if (lane == 0) t = (int)atomicAdd(tk, 1u);
-    return t;
-  };
   auto tile_key = [&](int ticket) -> long long { return (long long)(ntiles - 1 - ticket) * 32; };
   const u32x4* kbase = a.k + (size_t)unit * a.n_cap * CPR;
   const u32x4* vbase = a.v + (size_t)unit * a.n_cap * CPR;
@@ -210,8 +217,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   };
 #pragma unroll
   for (int j = 0; j < NL; ++j) { kraw[j] = u32x4{0u, 0u, 0u, 0u}; vraw[j] = u32x4{0u, 0u, 0u, 0u}; }
-  int t_cur = __builtin_amdgcn_readfirstlane(grab());
-  int t_nxt_raw = grab();
+  int t_cur = __builtin_amdgcn_readfirstlane(t_cur_raw);
   long long key0 = t_cur < ntiles ? tile_key(t_cur) : 0;
   if (t_cur < ntiles) {                                      // first tile: plain loads
     if constexpr (!CLAMP) {
@@ -232,6 +238,13 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
       }
     }
   }
+
+#pragma unroll
+  for (int it = 0; it < NFIT; ++it) {
+    const int i = tid + it * NW * 64;
+    if (i < NFRAG * 64) smem[i] = ftmp[it];
+  }
+  __syncthreads();
 
   // Results of a tile are stored one iteration later, right after the staging of the next
   // tile: global stores share the in-order counter of the loads, and stores issued while
