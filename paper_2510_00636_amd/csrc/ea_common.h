@@ -31,7 +31,7 @@ struct ScorePlan {
   int passes;   // ceil(G / GH); K is streamed once per pass
   int NW;       // wavefronts per workgroup
   int nfrag;    // 1 KiB fragments per (unit, pass)
-  int span;     // keys per workgroup
+  int span;     // keys per workgroup were the head split evenly (the kernel deals tiles by ticket)
   int nchunk;   // workgroups per unit = ceil(n / span)
   size_t lds_bytes;
 };

@@ -26,7 +26,6 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
   a.part = part;
   a.G = d.G;
   a.passes = sp.passes;
-  a.span = sp.span;
   a.nchunk = sp.nchunk;
   a.units = d.units();
   a.nfrag = sp.nfrag;

@@ -32,7 +32,7 @@ struct ScoreArgs {
   float* logits;
   float* vnorm;
   float2* part;
-  int G, passes, span, nchunk, units, nfrag;
+  int G, passes, nchunk, units, nfrag;     // nchunk: workgroups per (unit, pass)
   uint32_t* tickets;      // tickets + unit * ticket_stride + pass: tile counter, zero at launch
   int ticket_stride;
 };
