@@ -15,7 +15,7 @@ hipError_t launch_prep_frags(const Dims& d, const ScorePlan& sp, const float* mu
                              const float* sigma, uint4* frags, float* post, hipStream_t st);
 
 // ea_score.hip
-// tickets + unit * ticket_stride + pass: one tile counter per (unit, pass), zero at launch
+// tickets + unit * ticket_stride: 8 tile counters per pass of the unit (at most 64 passes), zero at launch
 hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
                              float* logits, float* vnorm, float2* part, uint32_t* tickets,

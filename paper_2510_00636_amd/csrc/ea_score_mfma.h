@@ -23,6 +23,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // a struct whose copies go through memcpy)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int kTicketWays = 8;
+
 struct ScoreArgs {
   const u32x4* k;
   const u32x4* v;
@@ -33,7 +35,7 @@ struct ScoreArgs {
   float* vnorm;
   float2* part;
   int G, passes, nchunk, units, nfrag;     // nchunk: workgroups per (unit, pass)
-  uint32_t* tickets;      // tickets + unit * ticket_stride + pass: tile counter, zero at launch
+  uint32_t* tickets;      // tickets + unit * ticket_stride + pass * kTicketWays + way: tile counters, zero at launch
   int ticket_stride;
 };
 
@@ -167,10 +169,16 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   // issue time to come back), and only then the fragments' way into LDS and the barrier: the
   // first tile travels while the workgroup assembles its fragments.
   const int ntiles = (int)((a.n + 31) / 32);
-  uint32_t* tk = a.tickets + (size_t)unit * a.ticket_stride + pass;
+  // Up to kTicketWays counters per (unit, pass), each dealing the tiles of one residue class, so
+  // that a head scored by hundreds of workgroups (few KV heads per call) does not queue up on one
+  // address: an atomic on one address takes about 13 ns.  A workgroup uses the counter of its
+  // index modulo the number of counters in use.
+  const int ways = max(1, min(kTicketWays, a.nchunk / 8));    // at least 8 workgroups per counter
+  const int way = chunk % ways;
+  uint32_t* tk = a.tickets + (size_t)unit * a.ticket_stride + pass * kTicketWays + way;
   auto grab = [&]() -> int {               // valid in lane 0; v_readfirstlane where it is used
     int t = 0;
-    if (lane == 0) t = (int)atomicAdd(tk, 1u);
+    if (lane == 0) t = (int)atomicAdd(tk, 1u) * ways + way;
     return t;
   };
   const int t_cur_raw = grab();
