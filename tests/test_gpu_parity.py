@@ -91,6 +91,20 @@ def test_score_ragged_sizes_and_capacity(n):
     P.check_scores(got, ref, 2e-3)
 
 
+@pytest.mark.parametrize("hq,hkv", [(8, 1), (16, 2), (3, 1)])
+def test_score_group_shapes(hq, hkv):
+    """One KV head scored by the whole grid (several tile counters), groups larger than one pass
+    holds (two passes over K for 8 query heads per KV head at d = 128), and an odd group."""
+    cfg = CONFIGS["c2"].with_(n_q_heads=hq, n_kv_heads=hkv)
+    lay = make_layer(cfg, n=9000 + 13, window=16)
+    rmu, rsg = _oracle_stats(cfg, lay)
+    mu32, sg32 = rmu.astype(np.float32), rsg.astype(np.float32)
+    for eps in (0.02, 0.0):
+        got = P.run_score(cfg, lay, mu32, sg32, eps)
+        ref = O.scores(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), sg32.astype(np.float64), eps)
+        P.check_scores(got, ref, 2e-3)
+
+
 def test_score_zero_covariance_and_zero_mean():
     cfg = CONFIGS["c2"].with_(n_q_heads=4, n_kv_heads=1)
     lay = make_layer(cfg, n=600, window=8)
