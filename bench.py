@@ -6,13 +6,16 @@ every layer of a synthetic Llama-3.1-8B-shaped cache (32 layers x 8 KV heads x 1
 head_dim 128, bf16, about 16 GiB of K+V), layer by layer through ea_compress_layer, at
 compression ratio 0.5.  Inputs are resident in HBM before the timed region; the cache is
 restored from a pristine copy between steps, outside the timed region (compaction is in place).
+Layers are independent, so they are issued round-robin on a few HIP streams (--streams, default 3),
+each with a workspace of its own; the whole step is bracketed by device synchronisation.
 
 Prints ONE JSON line: metric/value (G KV pairs scored+compacted per second), ms_per_step,
 `roofline` for the dominant kernel (score pass A, HBM-bound: it streams every K and V row
-once) with its average launch duration measured by HIP events on the launch stream, and
+once) with its average launch duration measured by HIP events on the launch stream in separate
+one-stream instrumented steps (the duration of the kernel running alone), and
 `cpu_baseline` (the fp64 oracle timed on this machine's host cores on one layer of the same input).
 
-    python bench.py [--steps K] [--warmup W] [--workload c3|c2|c4|c5] [--ratio R] [--layers L]
+    python bench.py [--steps K] [--warmup W] [--workload c3|c2|c4|c5] [--ratio R] [--layers L] [--streams S]
 """
 import argparse
 import json

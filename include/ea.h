@@ -14,7 +14,9 @@
  *     enqueue work on that stream and return; they never synchronise the host, create
  *     streams, allocate, free or keep device memory.  Scratch comes through `ws`
  *     (at least ea_workspace_bytes() bytes, 256-byte aligned, owned by the caller, contents
- *     undefined between calls).  Calls sharing one `ws` must be ordered on one stream.
+ *     undefined between calls).  Calls sharing one `ws` must be ordered on one stream; calls
+ *     on different streams need a workspace each and may then run concurrently (layers of a
+ *     cache are independent).
  *   - Errors are return codes; nothing aborts or throws across the ABI.  Argument errors are
  *     detected on the host before any launch, so outputs are untouched on EA_ERR_INVALID_ARG,
  *     EA_ERR_UNSUPPORTED and EA_ERR_WORKSPACE.  A failed launch returns EA_ERR_DEVICE.
