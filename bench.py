@@ -6,8 +6,10 @@ every layer of a synthetic Llama-3.1-8B-shaped cache (32 layers x 8 KV heads x 1
 head_dim 128, bf16, about 16 GiB of K+V), layer by layer through ea_compress_layer, at
 compression ratio 0.5.  Inputs are resident in HBM before the timed region; the cache is
 restored from a pristine copy between steps, outside the timed region (compaction is in place).
-Layers are independent, so they are issued round-robin on a few HIP streams (--streams, default 3),
-each with a workspace of its own; the whole step is bracketed by device synchronisation.
+Layers are independent and of one shape, so consecutive layers go to one call as a batch
+(--layer-batch, default 4: they are contiguous in memory and share positions and frequencies) and
+the calls are issued round-robin on a few HIP streams (--streams, default 3), each with a workspace
+of its own; the whole step is bracketed by device synchronisation.
 
 Prints ONE JSON line: metric/value (G KV pairs scored+compacted per second), ms_per_step,
 `roofline` for the dominant kernel (score pass A, HBM-bound: it streams every K and V row
@@ -15,7 +17,7 @@ once) with its average launch duration measured by HIP events on the launch stre
 one-stream instrumented steps (the duration of the kernel running alone), and
 `cpu_baseline` (the fp64 oracle timed on this machine's host cores on one layer of the same input).
 
-    python bench.py [--steps K] [--warmup W] [--workload c3|c2|c4|c5] [--ratio R] [--layers L] [--streams S]
+    python bench.py [--steps K] [--warmup W] [--workload c3|c2|c4|c5] [--ratio R] [--layers L] [--streams S] [--layer-batch LB]
 """
 import argparse
 import json
@@ -40,6 +42,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--epsilon", type=float, default=0.02)
+    ap.add_argument("--layer-batch", type=int, default=4,
+                    help="consecutive layers handed to one ea_compress_layer call as a batch (same shape, "
+                         "same positions, contiguous in memory): fewer, larger launches")
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the layers are spread over (each with its own workspace); layers "
                          "are independent, so the short latency-bound kernels of one layer overlap "
@@ -47,13 +52,13 @@ def parse():
     return ap.parse_args()
 
 
-def traffic_from_profile(name):
+def traffic_from_profile(name, layers_per_launch):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE / WRITE_SIZE runs), if one exists for this workload; else None."""
+    (FETCH_SIZE / WRITE_SIZE runs), if one exists for this workload and launch shape; else None."""
     path = os.path.join(ROOT, "profiles", "k_score_mfma_%s_pmc.txt" % name)
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
+            if line.startswith("traffic_bytes_per_launch[%d layers]:" % layers_per_launch):
                 return float(line.split(":")[1])
     except OSError:
         pass
@@ -81,7 +86,11 @@ def main():
     L = a.layers or cfg.layers
     B, Hq, Hkv, d, n, w = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n, cfg.window
     n_keep = ea.n_keep(n, a.ratio)
-    p = ea.make_params(B, Hq, Hkv, d, ea.EA_BF16, horizon_T=cfg.horizon_T, epsilon=a.epsilon)
+    LB = max(1, a.layer_batch)
+    while L % LB:
+        LB -= 1
+    p1 = ea.make_params(B, Hq, Hkv, d, ea.EA_BF16, horizon_T=cfg.horizon_T, epsilon=a.epsilon)
+    p = ea.make_params(B * LB, Hq, Hkv, d, ea.EA_BF16, horizon_T=cfg.horizon_T, epsilon=a.epsilon)
 
     dev = "cuda"
     k0 = torch.empty(L, B, Hkv, n, d, dtype=torch.bfloat16, device=dev)     # pristine copies
@@ -92,7 +101,7 @@ def main():
         lay = make_layer_device(cfg, l, out_k=k0[l], out_v=v0[l], out_q=q[l])
         inv = lay["inv_freq"]
     k, v = torch.empty_like(k0), torch.empty_like(v0)
-    ns = max(1, min(a.streams, L))
+    ns = max(1, min(a.streams, L // LB))
     wss = [torch.empty(ea.workspace_bytes(p, n, w), dtype=torch.uint8, device=dev) for _ in range(ns)]
     ws = wss[0]
     streams = [torch.cuda.Stream() for _ in range(ns)] if ns > 1 else [None]      # default priority
@@ -106,9 +115,9 @@ def main():
     def step():
         # layer l runs on stream l % ns with that stream's workspace; the caller synchronises
         # the device before and after a step
-        for l in range(L):
-            ea.compress_layer(p, q[l], w, q_pos0, inv, t_next, k[l], v[l], n, n, n_keep, None, None,
-                              wss[l % ns], stream=streams[l % ns])
+        for i, l in enumerate(range(0, L, LB)):
+            ea.compress_layer(p, q[l:l + LB], w, q_pos0, inv, t_next, k[l:l + LB], v[l:l + LB], n, n, n_keep,
+                              None, None, wss[i % ns], stream=streams[i % ns])
 
     for _ in range(a.warmup):
         restore()
@@ -130,27 +139,31 @@ def main():
     bytes_per_pair = 2 * d * 2 * (1 + 2 * f)                     # K,V read once + kept rows read+written
     path_hbm_frac = pairs * bytes_per_pair / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
-    # ---- per-stage durations with HIP events on the launch stream (instrumented steps)
+    # ---- per-stage durations with HIP events on the launch stream (instrumented steps: the same
+    #      calls as the timed steps, one after the other on one stream, so each kernel runs alone)
     stage = np.zeros(ea.binding.N_STAGES)
     nst = max(1, min(a.steps, 3))
+    ncall = L // LB
     for _ in range(nst):
         restore()
         torch.cuda.synchronize()
-        for l in range(L):
-            stage += np.array(ea.compress_layer_timed(p, q[l], w, q_pos0, inv, t_next, k[l], v[l], n, n,
-                                                      n_keep, ws))
-    stage /= nst * L                                              # ms per launch (= per layer)
+        for l in range(0, L, LB):
+            stage += np.array(ea.compress_layer_timed(p, q[l:l + LB], w, q_pos0, inv, t_next, k[l:l + LB],
+                                                      v[l:l + LB], n, n, n_keep, ws))
+    stage /= nst * ncall                                          # ms per launch (= per call of LB layers)
     score_ms = float(stage[2])
-    score_bytes = B * Hkv * n * 2 * d * 2                          # algorithmic: every K and V row once
+    score_bytes = LB * B * Hkv * n * 2 * d * 2                     # algorithmic: every K and V row once
     achieved = score_bytes / (score_ms * 1e-3) / 1e9
     G = Hq // Hkv
-    flops = B * Hkv * n * (G * (2 * d * d + 2 * d) + 2 * d)
+    flops = LB * B * Hkv * n * (G * (2 * d * d + 2 * d) + 2 * d)
     roofline = {"kernel": "k_score_mfma", "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic_from_profile(cfg.name),
+                "traffic": traffic_from_profile(cfg.name, LB),
                 "avg_launch_ms": round(score_ms, 4), "bytes_per_launch": score_bytes,
+                "layers_per_launch": LB,
                 "mfma_dense_tflops": round(flops / (score_ms * 1e-3) / 1e12, 1),
                 "mfma_frac_of_f16_peak": round(flops / (score_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}
+    stage /= LB                                                    # per layer from here on
     compact_bytes = B * Hkv * n_keep * 2 * d * 2 * 2
     stages = {nm: round(float(ms), 4) for nm, ms in zip(ea.STAGE_NAMES, stage)}
     stages["compact_GBs"] = round(compact_bytes / (float(stage[5]) * 1e-3) / 1e9, 1) if stage[5] > 0 else None
@@ -160,8 +173,8 @@ def main():
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
            "config": {"workload": "%s: %d layers x %d KV heads x %d tokens x d%d, Hq %d, window %d, "
-                                  "ratio %.2f (keep %d), eps %.2f, in place, layers spread over %d streams" %
-                                  (cfg.name, L, Hkv * B, n, d, Hq, w, a.ratio, n_keep, a.epsilon, ns),
+                                  "ratio %.2f (keep %d), eps %.2f, in place, %d layer(s) per call, calls spread over %d streams" %
+                                  (cfg.name, L, Hkv * B, n, d, Hq, w, a.ratio, n_keep, a.epsilon, LB, ns),
                       "pairs_per_step": pairs, "bytes_per_pair": bytes_per_pair},
            "path_hbm_frac": round(path_hbm_frac, 4),
            "stage_ms_per_layer": stages,
