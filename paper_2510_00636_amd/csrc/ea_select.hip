@@ -166,22 +166,28 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_count(SelArgs a) {
   }
 }
 
-// exclusive scan of one value per thread over the 256 threads of the workgroup
+// exclusive scan of one value per thread over the 256 threads of the workgroup: a shuffle scan
+// inside each wavefront, then the four wave totals through LDS
 __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* s_tmp, uint32_t* total) {
-  const int tid = threadIdx.x;
-  __syncthreads();
-  s_tmp[tid] = v;
-  __syncthreads();
-  for (int o = 1; o < kSelThreads; o <<= 1) {
-    uint32_t add = tid >= o ? s_tmp[tid - o] : 0;
-    __syncthreads();
-    s_tmp[tid] += add;
-    __syncthreads();
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
   }
-  const uint32_t incl = s_tmp[tid];
-  *total = s_tmp[kSelThreads - 1];
+  __syncthreads();                       // s_tmp may still be read from an earlier call
+  if (lane == 63) s_tmp[wave] = incl;
   __syncthreads();
-  return incl - v;
+  uint32_t before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kSelThreads / 64; ++w) {
+    const uint32_t t = s_tmp[w];
+    before += w < wave ? t : 0u;
+    tot += t;
+  }
+  *total = tot;
+  return before + incl - v;
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_sel_emit(SelArgs a) {
