@@ -66,6 +66,13 @@ __device__ __forceinline__ float sumsq_bf16x8(u32x4 r) {
   return s;
 }
 
+// x of lane l plus x of lane l ^ 32, in every lane: one v_permlane32_swap (it hands both
+// halves of the wavefront the other half's registers) instead of a trip through LDS.
+__device__ __forceinline__ float sum_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // x + (x of another lane of the same 16-lane row), selected by a DPP control word
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float x) {
@@ -408,7 +415,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 #pragma unroll
     for (int g = 0; g < GH; ++g) {
       float lg = partial[g] * pq[g] + lin[g];
-      lg += __shfl_xor(lg, 32);
+      lg = sum_halves(lg);
       lg_prev[g] = lg;
       if (valid && g0 + g < a.G) {
         float mn = fmaxf(m_run[g], lg);
