@@ -44,145 +44,232 @@ __global__ void k_rope_table(const double* __restrict__ inv_freq, long long q_po
 }
 
 // ---------------------------------------------------------------------------------------
-// One workgroup = 16 rows of one head's Sigma.  The window is processed in chunks of up to 128
-// samples: every thread issues all its 16-byte query loads and table loads of a chunk at once
-// (one memory latency per chunk instead of one per sample), writes the transformed samples
-// u~ to LDS, and the workgroup then forms column sums (first pass) or centred outer products
-// (second pass) from LDS.  A window of at most 128 samples is loaded only once.
-constexpr int kStatsRB = 16;    // Sigma rows per workgroup
-constexpr int kStatsWC = 128;   // samples per LDS chunk
+// One workgroup = 32 rows of one head's Sigma.  The window is read ONCE, in chunks of up to 64
+// samples: every thread issues all its 16-byte query loads and table loads of a chunk together
+// (one memory latency per chunk instead of one per sample; the next chunk's loads go out before
+// the current chunk's arithmetic), maps them to u~, subtracts the head's first sample u~_0 and
+// writes the result to LDS; the four wavefronts then add the chunk's outer products to their
+// 32 x 32 accumulator tiles with fp32 matrix-core instructions, two samples per instruction.
+// With x = u~ - u~_0,
+//     mean  = u~_0 + (1/w) sum_s x_s
+//     Sigma = (1/(w - ddof)) (sum_s x_s x_s^T - w xbar xbar^T)
+// exactly; the shift keeps |x| at the scale of the spread, so the subtraction of the second
+// term costs no accuracy even for channels whose mean is many standard deviations from zero.
+// Column sums are formed on the way in (each thread keeps the sums of the 16 channels of its
+// items, all of one channel group) and combined in a fixed order, so results are reproducible.
+constexpr int kStatsWC = 64;    // samples per LDS chunk
 
+// Channels of pair e of channel group g: ja for the first, jb for the second element of the pair.
+template <int D>
+__device__ __forceinline__ int stats_ja(int layout, int g, int e) { return layout ? 2 * (8 * g + e) : 8 * g + e; }
+template <int D>
+__device__ __forceinline__ int stats_jb(int layout, int g, int e) { return layout ? 2 * (8 * g + e) + 1 : 8 * g + e + D / 2; }
+
+// Loads of item (one sample, channel group g): the 8 pairs (qa[e], qb[e]) of the query row and
+// their 2x2 blocks tb[e] of the table row.
 template <int D, bool BF16>
-__device__ __forceinline__ void stats_load_chunk(const void* __restrict__ q_win, size_t qbase, int s0,
-                                                 int ns, int layout, const float2* __restrict__ tab,
-                                                 float* __restrict__ s_u) {
-  constexpr int HALF = D / 2, G8 = HALF / 8;          // groups of 8 channel pairs per sample
-  constexpr int ITEMS = kStatsWC * G8 / 256;          // (sample, group) items per thread
-  const int tid = threadIdx.x;
-  float qa[ITEMS][8], qb[ITEMS][8];
-  float2 tb[ITEMS][8];
+__device__ __forceinline__ void stats_load_item(const void* __restrict__ q_win, size_t row, int g, int layout,
+                                                const float2* __restrict__ tabrow, float (&qa)[8],
+                                                float (&qb)[8], float2 (&tb)[8]) {
+  constexpr int HALF = D / 2;
+  // half-split: channels 8g.. and HALF+8g..; interleaved: 16 consecutive channels = 8 pairs
+  const size_t oa = row + (layout ? 16 * g : 8 * g), ob = row + (layout ? 16 * g + 8 : HALF + 8 * g);
+  float xa[8], xb[8];
+  if (BF16) {
+    const uint4 ra = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + oa);
+    const uint4 rb = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + ob);
+    const uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb.x, rb.y, rb.z, rb.w};
 #pragma unroll
-  for (int it = 0; it < ITEMS; ++it) {
-    const int item = tid + it * 256, sl = item / G8, g = item % G8;
-    if (sl < ns) {
-      const size_t row = qbase + (size_t)(s0 + sl) * D;
-      // half-split: channels 8g.. and HALF+8g..; interleaved: 16 consecutive channels = 8 pairs
-      const size_t oa = row + (layout ? 16 * g : 8 * g), ob = row + (layout ? 16 * g + 8 : HALF + 8 * g);
-      float xa[8], xb[8];
-      if (BF16) {
-        const uint4 ra = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + oa);
-        const uint4 rb = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + ob);
-        const uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb.x, rb.y, rb.z, rb.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          xa[2 * e] = __uint_as_float(wa[e] << 16);
-          xa[2 * e + 1] = __uint_as_float(wa[e] & 0xffff0000u);
-          xb[2 * e] = __uint_as_float(wb[e] << 16);
-          xb[2 * e + 1] = __uint_as_float(wb[e] & 0xffff0000u);
-        }
-      } else {
-        const float4 a0 = *reinterpret_cast<const float4*>((const float*)q_win + oa);
-        const float4 a1 = *reinterpret_cast<const float4*>((const float*)q_win + oa + 4);
-        const float4 b0 = *reinterpret_cast<const float4*>((const float*)q_win + ob);
-        const float4 b1 = *reinterpret_cast<const float4*>((const float*)q_win + ob + 4);
-        xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w; xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
-        xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w; xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        // pair e of the group: (xa[e], xb[e]) half-split; (x[2e], x[2e+1]) of the 16 interleaved
-        qa[it][e] = layout ? (e < 4 ? xa[2 * e] : xb[2 * e - 8]) : xa[e];
-        qb[it][e] = layout ? (e < 4 ? xa[2 * e + 1] : xb[2 * e - 7]) : xb[e];
-      }
-      const float4* tp = reinterpret_cast<const float4*>(tab + (size_t)(s0 + sl) * HALF + 8 * g);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float4 t = tp[e];
-        tb[it][2 * e] = make_float2(t.x, t.y);
-        tb[it][2 * e + 1] = make_float2(t.z, t.w);
-      }
+    for (int e = 0; e < 4; ++e) {
+      xa[2 * e] = __uint_as_float(wa[e] << 16);
+      xa[2 * e + 1] = __uint_as_float(wa[e] & 0xffff0000u);
+      xb[2 * e] = __uint_as_float(wb[e] << 16);
+      xb[2 * e + 1] = __uint_as_float(wb[e] & 0xffff0000u);
     }
+  } else {
+    const float4 a0 = *reinterpret_cast<const float4*>((const float*)q_win + oa);
+    const float4 a1 = *reinterpret_cast<const float4*>((const float*)q_win + oa + 4);
+    const float4 b0 = *reinterpret_cast<const float4*>((const float*)q_win + ob);
+    const float4 b1 = *reinterpret_cast<const float4*>((const float*)q_win + ob + 4);
+    xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w; xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
+    xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w; xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
   }
 #pragma unroll
-  for (int it = 0; it < ITEMS; ++it) {
-    const int item = tid + it * 256, sl = item / G8, g = item % G8;
-    if (sl < ns) {
+  for (int e = 0; e < 8; ++e) {
+    // pair e of the group: (xa[e], xb[e]) half-split; (x[2e], x[2e+1]) of the 16 interleaved
+    qa[e] = layout ? (e < 4 ? xa[2 * e] : xb[2 * e - 8]) : xa[e];
+    qb[e] = layout ? (e < 4 ? xa[2 * e + 1] : xb[2 * e - 7]) : xb[e];
+  }
+  const float4* tp = reinterpret_cast<const float4*>(tabrow + 8 * g);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int c = 8 * g + e;
-        const int ja = layout ? 2 * c : c, jb = layout ? 2 * c + 1 : c + HALF;
-        s_u[sl * D + ja] = tb[it][e].x * qa[it][e] - tb[it][e].y * qb[it][e];
-        s_u[sl * D + jb] = tb[it][e].y * qa[it][e] + tb[it][e].x * qb[it][e];
-      }
-    }
+  for (int e = 0; e < 4; ++e) {
+    const float4 t = tp[e];
+    tb[2 * e] = make_float2(t.x, t.y);
+    tb[2 * e + 1] = make_float2(t.z, t.w);
   }
 }
+
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
 
 template <int D, bool BF16>
 __global__ __launch_bounds__(256) void k_stats(const void* __restrict__ q_win, int w, int layout,
                                                int ddof, const float2* __restrict__ tab,
                                                float* __restrict__ mu, float* __restrict__ sigma) {
-  constexpr int RG = 256 / D > 0 ? 256 / D : 1;   // row groups in the accumulation phase
-  constexpr int NO = kStatsRB / RG;               // Sigma rows per thread
+  constexpr int HALF = D / 2, G8 = HALF / 8;          // groups of 8 channel pairs per sample
+  constexpr int ITEMS = kStatsWC * G8 / 256;          // (sample, group) items per thread and chunk
+  constexpr int NCT = D / 32;                         // 32-column tiles across Sigma
+  constexpr int TPW = (NCT + 3) / 4;                  // tiles per wavefront
+  static_assert(256 % G8 == 0 && ITEMS >= 1, "one channel group per thread");
   extern __shared__ __align__(16) float s_dyn[];
-  float* s_u = s_dyn;                             // [kStatsWC][D]
-  float* s_mean = s_dyn + kStatsWC * D;           // [D]
-  const int head = blockIdx.x, rb = blockIdx.y, tid = threadIdx.x;
+  float* s_u = s_dyn;                                 // [kStatsWC][D]   x = u~ - u~_0 of the chunk
+  float* s_part = s_dyn + kStatsWC * D;               // [4][D]          column sums per wavefront
+  float* s_shift = s_part + 4 * D;                    // [D]             u~_0
+  float* s_xbar = s_shift + D;                        // [D]             (1/w) sum_s x_s
+  const int head = blockIdx.x, rb = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const size_t qbase = (size_t)head * w * D;
   const int nchunks = (w + kStatsWC - 1) / kStatsWC;
+  const int g = tid % G8;                             // the channel group of all this thread's items
 
-  // pass 1: column sums
-  float colsum = 0.f;
-  for (int ch = 0; ch < nchunks; ++ch) {
-    const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
-    if (ch > 0) __syncthreads();
-    stats_load_chunk<D, BF16>(q_win, qbase, s0, ns, layout, tab, s_u);
-    __syncthreads();
-    if (tid < D)
-      for (int sl = 0; sl < ns; ++sl) colsum += s_u[sl * D + tid];
-  }
-  if (tid < D) {
-    const float m = colsum / (float)w;
-    s_mean[tid] = m;
-    if (rb == 0) mu[(size_t)head * D + tid] = m;
-  }
-  __syncthreads();
-
-  // pass 2: centred outer products (the single chunk of a short window is still in LDS)
-  const int j = tid % D, rg = tid / D;
-  const int i0 = rb * kStatsRB + rg * NO;
-  float acc[NO];
+  // u~_0 for this thread's group
+  float sha[8], shb[8];
+  {
+    float qa[8], qb[8];
+    float2 tb[8];
+    stats_load_item<D, BF16>(q_win, qbase, g, layout, tab, qa, qb, tb);
 #pragma unroll
-  for (int o = 0; o < NO; ++o) acc[o] = 0.f;
-  for (int ch = 0; ch < nchunks; ++ch) {
-    const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
-    if (nchunks > 1) {
-      __syncthreads();
-      stats_load_chunk<D, BF16>(q_win, qbase, s0, ns, layout, tab, s_u);
-      __syncthreads();
+    for (int e = 0; e < 8; ++e) {
+      sha[e] = tb[e].x * qa[e] - tb[e].y * qb[e];
+      shb[e] = tb[e].y * qa[e] + tb[e].x * qb[e];
     }
-    for (int e = tid; e < ns * D; e += 256) s_u[e] -= s_mean[e % D];
-    __syncthreads();
-    if (rg < RG) {
-#pragma unroll 4
-      for (int sl = 0; sl < ns; ++sl) {
-        const float xj = s_u[sl * D + j];
-        const float4* xi = reinterpret_cast<const float4*>(s_u + sl * D + i0);
+    if (tid < G8) {
 #pragma unroll
-        for (int o4 = 0; o4 < NO / 4; ++o4) {
-          const float4 x = xi[o4];
-          acc[4 * o4 + 0] = fmaf(x.x, xj, acc[4 * o4 + 0]);
-          acc[4 * o4 + 1] = fmaf(x.y, xj, acc[4 * o4 + 1]);
-          acc[4 * o4 + 2] = fmaf(x.z, xj, acc[4 * o4 + 2]);
-          acc[4 * o4 + 3] = fmaf(x.w, xj, acc[4 * o4 + 3]);
-        }
+      for (int e = 0; e < 8; ++e) {
+        s_shift[stats_ja<D>(layout, g, e)] = sha[e];
+        s_shift[stats_jb<D>(layout, g, e)] = shb[e];
       }
     }
   }
-  const float inv = 1.0f / (float)(w - ddof);
-  if (rg < RG) {
+  float suma[8], sumb[8];
 #pragma unroll
-    for (int o = 0; o < NO; ++o) sigma[((size_t)head * D + i0 + o) * D + j] = acc[o] * inv;
+  for (int e = 0; e < 8; ++e) { suma[e] = 0.f; sumb[e] = 0.f; }
+
+  // Outer products on the matrix cores in fp32: v_mfma_f32_32x32x2_f32 adds, for two samples at a
+  // time, the 32 x 32 block  x[rows] x[cols]^T.  Lane l feeds row (or column) l % 32 of sample
+  // l / 32 of the pair; wavefront `wave` owns the column tiles wave, wave + 4, ...
+  const int r32 = lane & 31, hh = lane >> 5;
+  const int i0 = rb * 32;
+  floatx16_t acc[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+  float qa[ITEMS][8], qb[ITEMS][8];
+  float2 tb[ITEMS][8];
+  auto load_chunk = [&](int ch) __attribute__((always_inline)) {
+    const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int sl = (tid + it * 256) / G8;
+      if (sl < ns)
+        stats_load_item<D, BF16>(q_win, qbase + (size_t)(s0 + sl) * D, g, layout,
+                                 tab + (size_t)(s0 + sl) * HALF, qa[it], qb[it], tb[it]);
+    }
+  };
+  load_chunk(0);
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
+    if (ch > 0) __syncthreads();                      // the previous chunk has been consumed
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int sl = (tid + it * 256) / G8;
+      if (sl < ns) {
+        float xa[8], xb[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          xa[e] = tb[it][e].x * qa[it][e] - tb[it][e].y * qb[it][e] - sha[e];
+          xb[e] = tb[it][e].y * qa[it][e] + tb[it][e].x * qb[it][e] - shb[e];
+          suma[e] += xa[e];
+          sumb[e] += xb[e];
+        }
+        if (layout == 0) {                            // half-split: two runs of 8 consecutive channels
+          float4* pa = reinterpret_cast<float4*>(s_u + sl * D + 8 * g);
+          float4* pb = reinterpret_cast<float4*>(s_u + sl * D + HALF + 8 * g);
+          pa[0] = make_float4(xa[0], xa[1], xa[2], xa[3]);
+          pa[1] = make_float4(xa[4], xa[5], xa[6], xa[7]);
+          pb[0] = make_float4(xb[0], xb[1], xb[2], xb[3]);
+          pb[1] = make_float4(xb[4], xb[5], xb[6], xb[7]);
+        } else {                                      // interleaved: 16 consecutive channels
+          float4* pi = reinterpret_cast<float4*>(s_u + sl * D + 16 * g);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pi[e] = make_float4(xa[2 * e], xb[2 * e], xa[2 * e + 1], xb[2 * e + 1]);
+        }
+      }
+    }
+    __syncthreads();
+    if (ch + 1 < nchunks) load_chunk(ch + 1);         // in flight during the matrix-core loop
+    // four sample pairs per step: all their LDS reads first, then the MFMAs (samples past the
+    // chunk's end count as zero)
+    const int npair = (ns + 1) / 2;
+    for (int sp = 0; sp < npair; sp += 4) {
+      float av[4], bv[4][TPW];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int sl = 2 * (sp + u) + hh;
+        const bool ok = sl < ns;
+        av[u] = ok ? s_u[sl * D + i0 + r32] : 0.f;
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+          const int ct = wave + 4 * t;
+          bv[u][t] = (ok && ct < NCT) ? s_u[sl * D + ct * 32 + r32] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < TPW; ++t)
+          if (wave + 4 * t < NCT) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u][t], acc[t], 0, 0, 0);
+    }
+  }
+
+  // column sums: lanes that share a channel group (stride G8) first, then the four wavefronts
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+#pragma unroll
+    for (int o = G8; o < 64; o <<= 1) {
+      suma[e] += __shfl_xor(suma[e], o);
+      sumb[e] += __shfl_xor(sumb[e], o);
+    }
+  }
+  if (lane < G8) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      s_part[wave * D + stats_ja<D>(layout, g, e)] = suma[e];
+      s_part[wave * D + stats_jb<D>(layout, g, e)] = sumb[e];
+    }
+  }
+  __syncthreads();
+  const float invw = 1.0f / (float)w;
+  for (int c = tid; c < D; c += 256) {
+    const float xb = ((s_part[c] + s_part[D + c]) + (s_part[2 * D + c] + s_part[3 * D + c])) * invw;
+    s_xbar[c] = xb;
+    if (rb == 0) mu[(size_t)head * D + c] = s_shift[c] + xb;
+  }
+  __syncthreads();
+  // accumulator register v of lane (r32, hh) is row 8 (v / 4) + 4 hh + v % 4, column r32 of the tile
+  const float fw = (float)w, inv = 1.0f / (float)(w - ddof);
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    const int ct = wave + 4 * t;
+    if (ct < NCT) {
+      const int j = ct * 32 + r32;
+      const float xj = s_xbar[j];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = i0 + 8 * (v / 4) + 4 * hh + v % 4;
+        sigma[((size_t)head * D + i) * D + j] = (acc[t][v] - fw * s_xbar[i] * xj) * inv;
+      }
+    }
   }
 }
 
@@ -337,11 +424,11 @@ template <int D, bool BF16>
 static hipError_t launch_stats_one(const Dims& d, const void* q_win, int w, const float2* tab,
                                    float* mu, float* sigma, hipStream_t st) {
   auto kern = k_stats<D, BF16>;
-  const size_t lds = (size_t)(kStatsWC * D + D) * sizeof(float);
+  const size_t lds = (size_t)(kStatsWC * D + 6 * D) * sizeof(float);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  dim3 grid(d.qheads(), d.D / kStatsRB);
+  dim3 grid(d.qheads(), D / 32);
   kern<<<grid, 256, lds, st>>>(q_win, w, d.rope_layout, d.ddof, tab, mu, sigma);
   return hipGetLastError();
 }
