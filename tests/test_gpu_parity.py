@@ -39,6 +39,19 @@ def test_query_stats(name):
     P.check_stats(mu, sg, rmu, rsg)
 
 
+@pytest.mark.parametrize("w", [2, 63, 64, 65, 131, 4096])
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_query_stats_window_sizes(w, dt):
+    """Odd tails of the two-samples-per-instruction loop, chunk boundaries of the 64-sample
+    staging, and the largest window the entry point accepts."""
+    cfg = (CONFIGS["c2"] if dt == "bf16" else CONFIGS["c1"]).with_(n_q_heads=3, n_kv_heads=1)
+    lay = make_layer(cfg, n=max(w, 8) + 5, window=w)
+    for ddof in (0, 1):
+        mu, sg = P.run_query_stats(cfg, lay, ddof=ddof)
+        rmu, rsg = _oracle_stats(cfg, lay, ddof=ddof)
+        P.check_stats(mu, sg, rmu, rsg)
+
+
 @pytest.mark.parametrize("variant", ["interleaved", "ddof1", "pre_rope", "T1", "w1"])
 def test_query_stats_variants(variant):
     cfg = CONFIGS["c2"].with_(n_q_heads=4, n_kv_heads=2)
