@@ -228,7 +228,10 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   // + lane*16 + j*1024 so that the address arithmetic stays on the scalar unit.  K and V are
   // read once: the loads carry the non-temporal hint, which keeps them from pushing the logits
   // (read back by the finalize pass) and the fragments out of the caches -- 5 % on this kernel,
-  // 14 % on the finalize pass.
+  // 14 % on the finalize pass.  At d = 256 a KV head's query heads take one pass over K each
+  // (their fragments do not fit in LDS together); the passes run side by side, and there K is
+  // loaded with the default policy so that the second reader finds it in a cache (5 %).
+  constexpr bool kNtK = D <= 128;
   u32x4 kraw[NL], vraw[NL];
   auto tile_base = [&](long long k0) -> long long {          // first row actually loaded
     return (!CLAMP && k0 + 32 > a.n) ? a.n - 32 : k0;
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
       const u32x4* kp = kbase + tile_base(key0) * CPR;
       const u32x4* vp = vbase + tile_base(key0) * CPR;
 #pragma unroll
-      for (int j = 0; j < NL; ++j) kraw[j] = __builtin_nontemporal_load(&kp[j * 64 + lane]);
+      for (int j = 0; j < NL; ++j) kraw[j] = kNtK ? __builtin_nontemporal_load(&kp[j * 64 + lane]) : kp[j * 64 + lane];
       if (do_v) {
 #pragma unroll
         for (int j = 0; j < NL; ++j) vraw[j] = __builtin_nontemporal_load(&vp[j * 64 + lane]);
@@ -404,7 +407,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
         static_for<2 * NL>([&](auto i_) {
           constexpr int i = decltype(i_)::value;
           if constexpr (f < NS && load_slot<NX, NS, NL>(i) == f) {
-            if constexpr (i < NL) kraw[i] = __builtin_nontemporal_load(&kp_n[i * kj + kl]);
+            if constexpr (i < NL) kraw[i] = kNtK ? __builtin_nontemporal_load(&kp_n[i * kj + kl]) : kp_n[i * kj + kl];
             else vraw[i - NL] = __builtin_nontemporal_load(&vp_n[(i - NL) * vj + vl]);
           }
         });
