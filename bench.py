@@ -170,6 +170,7 @@ def main():
 
     out = {"metric": "KV pairs scored+compacted/sec", "value": round(value, 4), "unit": "G pairs/s",
            "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
+           "ms_per_step_p50": round(1e3 * float(np.median(times)), 4), "ms_per_step_max": round(1e3 * max(times), 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
            "config": {"workload": "%s: %d layers x %d KV heads x %d tokens x d%d, Hq %d, window %d, "
