@@ -1,8 +1,9 @@
 """Full-size parity in the launch configuration bench.py times: one layer of the
 Llama-3.1-8B-shaped 131072-token cache (8 KV heads, 32 query heads, d 128, window 128, keep
-50 %), generated on the device and downloaded so the oracle sees the same bits.  The oracle
-is fast enough here to check every one of the 1,048,576 scores, the kept sets and the
-compacted bytes, not just a sample."""
+25 / 50 / 75 %), four such layers as one batch on side streams, one layer of the d-256 four-sequence
+shape and one decode-time pass, all generated on the device and downloaded so the oracle sees the
+same bits.  The oracle is fast enough here to check every score, the kept sets and the compacted
+bytes, not just a sample."""
 import numpy as np
 import pytest
 
@@ -13,15 +14,12 @@ from tests import parity as P
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("ratio,eps", [(0.5, 0.02), (0.75, 0.0), (0.25, 0.02)])
-def test_c3_layer_full_size(ratio, eps):
+def _layer_full_size(cfg, layer, n_keep, eps):
     import torch
     import paper_2510_00636_amd as ea
     from ea_inputs.device import make_layer_device
-    cfg = CONFIGS["c3"]
-    lay = make_layer_device(cfg, layer=int(ratio * 100) % 32)
+    lay = make_layer_device(cfg, layer=layer)
     n, w = lay["n"], lay["window"]
-    n_keep = ea.n_keep(n, ratio)
     host = dict(q_win=P.to_host(lay["q_win"]), k=P.to_host(lay["k"]), v=P.to_host(lay["v"]))
     p = ea.make_params(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, ea.EA_BF16,
                        horizon_T=cfg.horizon_T, epsilon=eps)
@@ -41,6 +39,26 @@ def test_c3_layer_full_size(ratio, eps):
     P.check_compaction(got["k"], got["v"], host["k"], host["v"], got["idx"], n_keep)
     # rows past n_keep are untouched
     assert np.array_equal(got["k"][:, :, n_keep:], host["k"][:, :, n_keep:])
+
+
+@pytest.mark.parametrize("ratio,eps", [(0.5, 0.02), (0.75, 0.0), (0.25, 0.02)])
+def test_c3_layer_full_size(ratio, eps):
+    import paper_2510_00636_amd as ea
+    cfg = CONFIGS["c3"]
+    _layer_full_size(cfg, int(ratio * 100) % 32, ea.n_keep(cfg.n, ratio), eps)
+
+
+def test_c4_layer_full_size():
+    """Head dimension 256, four sequences, two query heads per KV head (two passes over K)."""
+    cfg = CONFIGS["c4"]
+    _layer_full_size(cfg, 47, cfg.n // 2, 0.02)
+
+
+def test_c5_layer_full_size():
+    """The decode-time pass: 4608 cached tokens back to 4096, statistics over 512 queries,
+    five query heads per KV head."""
+    cfg = CONFIGS["c5"]
+    _layer_full_size(cfg, 0, 4096, 0.02)
 
 
 def test_c3_four_layers_as_one_batch_on_side_streams():
