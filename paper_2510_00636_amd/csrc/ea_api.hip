@@ -198,7 +198,8 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
                      clear_words)) != EA_OK)
     return s;
   if (ev) EA_TRY(hipEventRecord(ev[1], st));
-  if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores, n_keep > 0 ? hist : nullptr, true, w, L, st,
+  if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores,
+                     n_keep > 0 && !select_in_one_launch(n) ? hist : nullptr, true, w, L, st,
                      ev ? ev + 2 : nullptr)) != EA_OK)
     return s;
   if (ev) EA_TRY(hipEventRecord(ev[4], st));

@@ -29,6 +29,10 @@ hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int log
                            uint32_t* hist0, hipStream_t st);
 
 // ea_select.hip
+// heads this short are selected by one workgroup per unit out of LDS, in one launch (no global
+// histograms: hist0 from the finalize pass is not needed then)
+constexpr int64_t kSelSmallMax = 32768;
+inline bool select_in_one_launch(int64_t n) { return n <= kSelSmallMax; }
 hipError_t launch_select(const Dims& d, const float* scores, int64_t n, int64_t n_keep, int32_t* idx,
                          uint32_t* hist, uint32_t* blk, bool hist0_done, hipStream_t st);
 hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st);

@@ -252,6 +252,94 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_emit(SelArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Short heads (n <= kSelSmallMax): the whole head fits in LDS, so one workgroup per unit does
+// all of the above in one launch -- scores are read from memory once, the three histograms and
+// the emit pass work on the LDS copy.  Same result as the multi-launch path, bit for bit.
+constexpr int kSelSmallThreads = 1024;
+
+// exclusive scan of one value per thread over the 1024 threads of the workgroup
+__device__ uint32_t block_excl_scan_1024(uint32_t v, uint32_t* s_w, uint32_t* total) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  __syncthreads();                       // s_w may still be read from an earlier call
+  if (lane == 63) s_w[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kSelSmallThreads / 64; ++w) {
+    const uint32_t t = s_w[w];
+    before += w < wave ? t : 0u;
+    tot += t;
+  }
+  *total = tot;
+  return before + incl - v;
+}
+
+__global__ __launch_bounds__(kSelSmallThreads) void k_sel_small(SelArgs a) {
+  extern __shared__ __align__(16) uint32_t s_dyn[];
+  __shared__ uint32_t s_w[kSelSmallThreads / 64];
+  __shared__ uint32_t s_res[2];
+  const int tid = threadIdx.x, lane = tid & 63, unit = blockIdx.x, n = (int)a.n;
+  uint32_t* s_hist = s_dyn;                       // [2048]
+  uint32_t* s_sc = s_dyn + kSelBins;              // [n] score bit patterns
+  const uint32_t* sc = reinterpret_cast<const uint32_t*>(a.scores) + (size_t)unit * a.n;
+
+  uint32_t prefix = 0, rem = a.n_keep;
+#pragma unroll
+  for (int P = 0; P < 3; ++P) {
+    for (int i = tid; i < kSelBins; i += kSelSmallThreads) s_hist[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += kSelSmallThreads) {
+      uint32_t u;
+      if (P == 0) { u = sc[i]; s_sc[i] = u; } else { u = s_sc[i]; }
+      if (P == 0) atomicAdd(&s_hist[u >> 21], 1u);
+      if (P == 1 && (u >> 21) == prefix) atomicAdd(&s_hist[(u >> 10) & 2047u], 1u);
+      if (P == 2 && (u >> 10) == prefix) atomicAdd(&s_hist[u & 1023u], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {
+      uint32_t r;
+      const int b = find_bin_wave(s_hist, P == 2 ? 1024 : 2048, rem, &r, lane);
+      if (lane == 0) { s_res[0] = (prefix << (P == 2 ? 10 : 11)) | (uint32_t)b; s_res[1] = r; }
+    }
+    __syncthreads();
+    prefix = s_res[0];
+    rem = s_res[1];
+    __syncthreads();
+  }
+  const uint32_t T = prefix, q = rem;             // threshold pattern, ties at T to keep
+
+  // every thread owns a contiguous run of positions, so "first q ties by index" is a scan
+  const int per = (n + kSelSmallThreads - 1) / kSelSmallThreads;
+  const int i0 = min(tid * per, n), i1 = min(i0 + per, n);
+  uint32_t gt = 0, eq = 0;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t u = s_sc[i];
+    gt += u > T;
+    eq += u == T;
+  }
+  uint32_t tot;
+  uint32_t eq_before = block_excl_scan_1024(eq, s_w, &tot);
+  const uint32_t room = q > eq_before ? q - eq_before : 0u;
+  uint32_t pos = block_excl_scan_1024(gt + (eq < room ? eq : room), s_w, &tot);
+  int32_t* out = a.idx + (size_t)unit * a.n_keep;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t u = s_sc[i];
+    const bool k = u > T || (u == T && eq_before < q);
+    if (u == T) ++eq_before;
+    if (k) {
+      if (pos < a.n_keep) out[pos] = (int32_t)i;
+      ++pos;
+    }
+  }
+}
+
 hipError_t launch_select(const Dims& d, const float* scores, int64_t n, int64_t n_keep, int32_t* idx,
                          uint32_t* hist, uint32_t* blk, bool hist0_done, hipStream_t st) {
   SelArgs a;
@@ -262,6 +350,14 @@ hipError_t launch_select(const Dims& d, const float* scores, int64_t n, int64_t 
   a.blk = blk;
   a.idx = idx;
   a.nblk = (int)((n + kSelBlock - 1) / kSelBlock);
+  if (select_in_one_launch(n)) {
+    const size_t lds = ((size_t)kSelBins + (size_t)n + 4) * sizeof(uint32_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_sel_small),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    k_sel_small<<<d.units(), kSelSmallThreads, lds, st>>>(a);
+    return hipGetLastError();
+  }
   dim3 grid(d.units(), a.nblk);
   if (!hist0_done) k_sel_hist<0><<<grid, kSelThreads, 0, st>>>(a);
   k_sel_hist<1><<<grid, kSelThreads, 0, st>>>(a);

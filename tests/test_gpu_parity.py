@@ -145,8 +145,11 @@ def test_score_c2_full_size():
 
 # ------------------------------------------------------------------------------ ea_select
 @pytest.mark.parametrize("n,n_keep", [(1, 1), (1, 0), (5, 3), (4096, 2048), (4097, 1), (5000, 4999),
-                                      (5000, 5000), (20000, 7), (70000, 35000)])
+                                      (5000, 5000), (20000, 7), (32768, 30000), (32769, 1), (32769, 32768),
+                                      (70000, 35000), (70001, 69999)])
 def test_select_exact(n, n_keep):
+    # heads of up to 32768 scores are selected by one workgroup out of LDS, longer ones by the
+    # multi-launch histogram path: sizes on both sides of the switch
     cfg = CONFIGS["c2"].with_(batch=2, n_kv_heads=3, n_q_heads=3)
     r = np.random.default_rng(n * 7 + n_keep)
     sc = np.exp(r.standard_normal((2, 3, n))).astype(np.float32)
@@ -165,6 +168,11 @@ def test_select_denormal_and_huge_scores():
     sc = np.concatenate([r.random(3000) * 1e-42, r.random(3000) * 3e38, [0.0] * 50]).astype(np.float32)
     sc = r.permutation(sc)[None, None]
     for kk in (1, 3000, 3025, 6049):
+        got = P.run_select(cfg, sc, kk)
+        assert np.array_equal(got.astype(np.int64), O.select(sc.astype(np.float64), kk))
+    # the same values repeated past the single-workgroup limit: the multi-launch path
+    sc = np.tile(sc, (1, 1, 6))
+    for kk in (1, 18000, 18150, 36299):
         got = P.run_select(cfg, sc, kk)
         assert np.array_equal(got.astype(np.int64), O.select(sc.astype(np.float64), kk))
 
