@@ -65,20 +65,40 @@ __device__ __forceinline__ int stats_ja(int layout, int g, int e) { return layou
 template <int D>
 __device__ __forceinline__ int stats_jb(int layout, int g, int e) { return layout ? 2 * (8 * g + e) + 1 : 8 * g + e + D / 2; }
 
-// Loads of item (one sample, channel group g): the 8 pairs (qa[e], qb[e]) of the query row and
-// their 2x2 blocks tb[e] of the table row.
+// One item = one sample's channel group g: 8 pairs (qa[e], qb[e]) of the query row and their 2x2
+// blocks tb[e] of the table row.  An item is fetched as raw words (bf16 rows stay packed, half
+// the registers, while the loads are in flight) and unpacked where it is used.
+template <bool BF16>
+struct StatsRaw {
+  uint4 w[BF16 ? 2 : 4];
+  float4 t[4];
+};
 template <int D, bool BF16>
-__device__ __forceinline__ void stats_load_item(const void* __restrict__ q_win, size_t row, int g, int layout,
-                                                const float2* __restrict__ tabrow, float (&qa)[8],
-                                                float (&qb)[8], float2 (&tb)[8]) {
+__device__ __forceinline__ void stats_fetch_item(const void* __restrict__ q_win, size_t row, int g, int layout,
+                                                 const float2* __restrict__ tabrow, StatsRaw<BF16>& raw) {
   constexpr int HALF = D / 2;
   // half-split: channels 8g.. and HALF+8g..; interleaved: 16 consecutive channels = 8 pairs
   const size_t oa = row + (layout ? 16 * g : 8 * g), ob = row + (layout ? 16 * g + 8 : HALF + 8 * g);
+  if (BF16) {
+    raw.w[0] = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + oa);
+    raw.w[1] = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + ob);
+  } else {
+    raw.w[0] = *reinterpret_cast<const uint4*>((const float*)q_win + oa);
+    raw.w[1] = *reinterpret_cast<const uint4*>((const float*)q_win + oa + 4);
+    raw.w[BF16 ? 0 : 2] = *reinterpret_cast<const uint4*>((const float*)q_win + ob);
+    raw.w[BF16 ? 1 : 3] = *reinterpret_cast<const uint4*>((const float*)q_win + ob + 4);
+  }
+  const float4* tp = reinterpret_cast<const float4*>(tabrow + 8 * g);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) raw.t[e] = tp[e];
+}
+template <bool BF16>
+__device__ __forceinline__ void stats_unpack_item(const StatsRaw<BF16>& raw, int layout, float (&qa)[8],
+                                                  float (&qb)[8], float2 (&tb)[8]) {
   float xa[8], xb[8];
   if (BF16) {
-    const uint4 ra = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + oa);
-    const uint4 rb = *reinterpret_cast<const uint4*>((const uint16_t*)q_win + ob);
-    const uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb.x, rb.y, rb.z, rb.w};
+    const uint32_t wa[4] = {raw.w[0].x, raw.w[0].y, raw.w[0].z, raw.w[0].w};
+    const uint32_t wb[4] = {raw.w[1].x, raw.w[1].y, raw.w[1].z, raw.w[1].w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       xa[2 * e] = __uint_as_float(wa[e] << 16);
@@ -87,12 +107,11 @@ __device__ __forceinline__ void stats_load_item(const void* __restrict__ q_win, 
       xb[2 * e + 1] = __uint_as_float(wb[e] & 0xffff0000u);
     }
   } else {
-    const float4 a0 = *reinterpret_cast<const float4*>((const float*)q_win + oa);
-    const float4 a1 = *reinterpret_cast<const float4*>((const float*)q_win + oa + 4);
-    const float4 b0 = *reinterpret_cast<const float4*>((const float*)q_win + ob);
-    const float4 b1 = *reinterpret_cast<const float4*>((const float*)q_win + ob + 4);
-    xa[0] = a0.x; xa[1] = a0.y; xa[2] = a0.z; xa[3] = a0.w; xa[4] = a1.x; xa[5] = a1.y; xa[6] = a1.z; xa[7] = a1.w;
-    xb[0] = b0.x; xb[1] = b0.y; xb[2] = b0.z; xb[3] = b0.w; xb[4] = b1.x; xb[5] = b1.y; xb[6] = b1.z; xb[7] = b1.w;
+    const uint4 a0 = raw.w[0], a1 = raw.w[1], b0 = raw.w[BF16 ? 0 : 2], b1 = raw.w[BF16 ? 1 : 3];
+    const uint32_t wa[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+    const uint32_t wb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { xa[e] = __uint_as_float(wa[e]); xb[e] = __uint_as_float(wb[e]); }
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -100,19 +119,23 @@ __device__ __forceinline__ void stats_load_item(const void* __restrict__ q_win, 
     qa[e] = layout ? (e < 4 ? xa[2 * e] : xb[2 * e - 8]) : xa[e];
     qb[e] = layout ? (e < 4 ? xa[2 * e + 1] : xb[2 * e - 7]) : xb[e];
   }
-  const float4* tp = reinterpret_cast<const float4*>(tabrow + 8 * g);
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const float4 t = tp[e];
-    tb[2 * e] = make_float2(t.x, t.y);
-    tb[2 * e + 1] = make_float2(t.z, t.w);
+    tb[2 * e] = make_float2(raw.t[e].x, raw.t[e].y);
+    tb[2 * e + 1] = make_float2(raw.t[e].z, raw.t[e].w);
   }
 }
-
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 
+// Register budget: three workgroups per CU at d <= 128 (168 registers), two at d = 256 (240),
+// without spills for bf16 input (prefetched items stay packed).  With the compiler's own choice
+// (184 / 356 registers: two / one workgroup per CU) the 640 workgroups of a decode-shape call
+// did not fit on the chip at once, and the d = 256 shape had nothing to overlap its staging
+// with: 25 -> 15 us and 74 -> 26 us per layer.  A budget met only by spilling is no use here: a
+// kernel that needs scratch memory costs some 10 us more per launch when several streams are
+// in use.
 template <int D, bool BF16>
-__global__ __launch_bounds__(256) void k_stats(const void* __restrict__ q_win, int w, int layout,
+__global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* __restrict__ q_win, int w, int layout,
                                                int ddof, const float2* __restrict__ tab,
                                                float* __restrict__ mu, float* __restrict__ sigma) {
   constexpr int HALF = D / 2, G8 = HALF / 8;          // groups of 8 channel pairs per sample
@@ -135,7 +158,9 @@ __global__ __launch_bounds__(256) void k_stats(const void* __restrict__ q_win, i
   {
     float qa[8], qb[8];
     float2 tb[8];
-    stats_load_item<D, BF16>(q_win, qbase, g, layout, tab, qa, qb, tb);
+    StatsRaw<BF16> raw0;
+    stats_fetch_item<D, BF16>(q_win, qbase, g, layout, tab, raw0);
+    stats_unpack_item<BF16>(raw0, layout, qa, qb, tb);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       sha[e] = tb[e].x * qa[e] - tb[e].y * qb[e];
@@ -164,16 +189,15 @@ __global__ __launch_bounds__(256) void k_stats(const void* __restrict__ q_win, i
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
 
-  float qa[ITEMS][8], qb[ITEMS][8];
-  float2 tb[ITEMS][8];
+  StatsRaw<BF16> raw[ITEMS];
   auto load_chunk = [&](int ch) __attribute__((always_inline)) {
     const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
       const int sl = (tid + it * 256) / G8;
       if (sl < ns)
-        stats_load_item<D, BF16>(q_win, qbase + (size_t)(s0 + sl) * D, g, layout,
-                                 tab + (size_t)(s0 + sl) * HALF, qa[it], qb[it], tb[it]);
+        stats_fetch_item<D, BF16>(q_win, qbase + (size_t)(s0 + sl) * D, g, layout,
+                                  tab + (size_t)(s0 + sl) * HALF, raw[it]);
     }
   };
   load_chunk(0);
@@ -184,11 +208,13 @@ __global__ __launch_bounds__(256) void k_stats(const void* __restrict__ q_win, i
     for (int it = 0; it < ITEMS; ++it) {
       const int sl = (tid + it * 256) / G8;
       if (sl < ns) {
-        float xa[8], xb[8];
+        float qa[8], qb[8], xa[8], xb[8];
+        float2 tb[8];
+        stats_unpack_item<BF16>(raw[it], layout, qa, qb, tb);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          xa[e] = tb[it][e].x * qa[it][e] - tb[it][e].y * qb[it][e] - sha[e];
-          xb[e] = tb[it][e].y * qa[it][e] + tb[it][e].x * qb[it][e] - shb[e];
+          xa[e] = tb[e].x * qa[e] - tb[e].y * qb[e] - sha[e];
+          xb[e] = tb[e].y * qa[e] + tb[e].x * qb[e] - shb[e];
           suma[e] += xa[e];
           sumb[e] += xb[e];
         }
