@@ -343,7 +343,9 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     float lin[GH], partial[GH], vsq = 0.f;
     static_for<GH>([&](auto g_) { partial[decltype(g_)::value] = 0.f; lin[decltype(g_)::value] = 0.f; });
     {
-      constexpr int NX = 2 * NKS, NS = NX + GH * NF, NT = GH * NJT, PD = EA_FRAG_PREFETCH;
+      // (the five-head instance prefetches one fragment less: with four it spills, and a kernel that
+      // needs scratch memory pays for it at every launch)
+      constexpr int NX = 2 * NKS, NS = NX + GH * NF, NT = GH * NJT, PD = GH >= 5 ? 3 : EA_FRAG_PREFETCH;
       half8 fb[PD + 1];
       floatx16 ex, accb[3];
       static_for<PD>([&](auto i_) {
