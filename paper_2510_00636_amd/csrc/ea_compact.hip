@@ -68,7 +68,7 @@ template <int RB>
 __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   constexpr int CPR = RB / 16;                 // 16-byte pieces per row
   constexpr int NLD = kCompactRows * CPR / 256;
-  __shared__ int s_c, s_lo, s_hi;
+  __shared__ int s_c, s_lo, s_hi, s_ident;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool control = wave == 4;
@@ -88,19 +88,21 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   const int32_t* idx = a.idx + (size_t)unit * a.n_keep;
   const u32x4* src = a.src[tensor] + (size_t)unit * a.n_cap * CPR;
   u32x4* dst = a.dst[tensor] + (size_t)unit * a.n_cap * CPR;
-  // rows are strictly ascending with idx[j] >= j, so idx[j1-1] == j1-1 means nothing moves
-  const bool identity = a.inplace && idx[j1 - 1] == j1 - 1;
+  // Rows are strictly ascending with idx[j] >= j, so idx[j1-1] == j1-1 means nothing moves.  Only
+  // the control wavefront looks this up; the movers request their rows at once (waiting for the
+  // answer would put one more memory round trip in front of every chunk) and learn it, through
+  // s_ident, at the barrier before the stores.
+  bool identity = false;
+  if (control && a.inplace) identity = idx[j1 - 1] == j1 - 1;
 
   u32x4 buf[NLD];
   if (!control) {
-    if (!identity) {
 #pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int e = tid + 256 * i, row = e / CPR, col = e % CPR;
-        // a malformed index can never leave the tensor: clamp to [0, n)
-        // rows are read once and written once: non-temporal hints on both (4 % on this kernel)
-        if (j0 + row < j1) buf[i] = __builtin_nontemporal_load(&src[(size_t)min(max(idx[j0 + row], 0), a.n - 1) * CPR + col]);
-      }
+    for (int i = 0; i < NLD; ++i) {
+      const int e = tid + 256 * i, row = e / CPR, col = e % CPR;
+      // a malformed index can never leave the tensor: clamp to [0, n)
+      // rows are read once and written once: non-temporal hints on both (4 % on this kernel)
+      if (j0 + row < j1) buf[i] = __builtin_nontemporal_load(&src[(size_t)min(max(idx[j0 + row], 0), a.n - 1) * CPR + col]);
     }
     if (a.inplace) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // rows are in registers
   } else if (a.inplace && !identity) {
@@ -110,6 +112,7 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
     if (lane == 0) { s_lo = lo; s_hi = hi; }
   }
   if (a.inplace) {
+    if (control && lane == 0) s_ident = identity;
     __syncthreads();                 // every mover's loads have landed
     if (control) {
       // Relaxed, device-scope flag: what it guards are this chunk's *loads*, which have
@@ -124,6 +127,7 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
           __builtin_amdgcn_s_sleep(4);
     }
     __syncthreads();                 // stores are issued only after every awaited flag was seen
+    identity = s_ident != 0;
   }
   if (!control && !identity) {
 #pragma unroll

@@ -192,6 +192,7 @@ __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* s_tmp, uint32_t* total
 
 __global__ __launch_bounds__(kSelThreads) void k_sel_emit(SelArgs a) {
   __shared__ uint32_t s_tmp[258];
+  __shared__ int32_t s_idx[kSelBlock];
   __shared__ uint32_t s_base[2];
   const int tid = threadIdx.x, unit = blockIdx.x, blk = blockIdx.y;
   const uint32_t* slot = a.hist + ((size_t)unit * 3 + 2) * kSelBins + 1024;
@@ -242,14 +243,15 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_emit(SelArgs a) {
     keepmask |= (uint32_t)k << j;
     nk += k;
   }
-  uint32_t pos = base_kept + block_excl_scan(nk, s_tmp, &tot);
-  int32_t* out = a.idx + (size_t)unit * a.n_keep;
+  // kept positions of the block are gathered in LDS and written out as one contiguous run
+  uint32_t lp = block_excl_scan(nk, s_tmp, &tot);
 #pragma unroll
   for (int j = 0; j < kSelPer; ++j)
-    if ((keepmask >> j) & 1u) {
-      if (pos < a.n_keep) out[pos] = (int32_t)(i0 + j);
-      ++pos;
-    }
+    if ((keepmask >> j) & 1u) s_idx[lp++] = (int32_t)(i0 + j);
+  __syncthreads();
+  int32_t* out = a.idx + (size_t)unit * a.n_keep;
+  for (uint32_t t = tid; t < tot; t += kSelThreads)
+    if (base_kept + t < a.n_keep) out[base_kept + t] = s_idx[t];
 }
 
 // ---------------------------------------------------------------------------------------
