@@ -97,12 +97,19 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
 
   u32x4 buf[NLD];
   if (!control) {
+    // First every index, then every row, none of them under a per-thread condition: a load
+    // inside "if (row < j1)" is followed by a wait for everything in flight, which made the
+    // eight index -> row pairs of a thread sixteen round trips in a row.  Pieces past the end of
+    // a ragged last chunk load its last row again and are not stored.
+    int srow[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) srow[i] = idx[min(j0 + (tid + 256 * i) / CPR, j1 - 1)];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int e = tid + 256 * i, row = e / CPR, col = e % CPR;
+      const int col = (tid + 256 * i) % CPR;
       // a malformed index can never leave the tensor: clamp to [0, n)
       // rows are read once and written once: non-temporal hints on both (4 % on this kernel)
-      if (j0 + row < j1) buf[i] = __builtin_nontemporal_load(&src[(size_t)min(max(idx[j0 + row], 0), a.n - 1) * CPR + col]);
+      buf[i] = __builtin_nontemporal_load(&src[(size_t)min(max(srow[i], 0), a.n - 1) * CPR + col]);
     }
     if (a.inplace) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // rows are in registers
   } else if (a.inplace && !identity) {
