@@ -14,7 +14,7 @@ namespace ea {
 constexpr int kMaxWindow = 4096;
 constexpr int kSelBins = 2048;        // radix-select digit width: 11 + 11 + 10 bits
 constexpr int kSelBlock = 4096;       // scores per workgroup in the select passes
-constexpr int kCompactRows = 128;    // destination rows per workgroup chunk in ea_compact
+constexpr int kCompactRows = 96;     // destination rows per workgroup chunk in ea_compact (not a power of two on purpose)
 
 struct Dims {
   int B, Hq, Hkv, G, D, half;

@@ -55,8 +55,8 @@ __device__ int first_true(int c, int lane, Pred pred) {
   return hi;
 }
 
-// RB = row bytes.  Four mover wavefronts carry kCompactRows rows (RB/32 16-byte pieces per
-// thread); a fifth, control, wavefront takes the ticket, finds the chunks to wait for while
+// RB = row bytes.  Four mover wavefronts carry kCompactRows rows (kCompactRows * RB / 4096
+// 16-byte pieces per thread); a fifth, control, wavefront takes the ticket, finds the chunks to wait for while
 // the movers' loads are in flight, publishes this chunk's flag and polls the others.
 //
 // Tickets are per (unit, tensor): a workgroup serves tensor blockIdx % (2*units) and draws its
