@@ -205,12 +205,31 @@ __global__ __launch_bounds__(256) void k_finalize(const LT* __restrict__ logits,
   __syncthreads();
   const long long base = (long long)blockIdx.y * 1024;
   const LT invG = (LT)1 / (LT)G;
+  // The four keys of a thread go through the heads together and no load sits under a condition
+  // (indices past the end are clamped): loads inside "if (i < n)" come back one at a time.
+  long long ic[4];
+  float vn[4];
+  LT acc[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    ic[it] = min(base + it * 256 + tid, n - 1);
+    vn[it] = vnorm[(size_t)unit * n + ic[it]];
+    acc[it] = 0;
+  }
+  for (int g = 0; g < G; ++g) {
+    const LT* lp = logits + ((size_t)unit * G + g) * n;
+    const LT lse = s_lse[g];
+    LT lv[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) lv[it] = lp[ic[it]];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) acc[it] += ea_exp(lv[it] - lse);
+  }
+#pragma unroll
   for (int it = 0; it < 4; ++it) {
     const long long i = base + it * 256 + tid;
     if (i < n) {
-      LT acc = 0;
-      for (int g = 0; g < G; ++g) acc += ea_exp(logits[((size_t)unit * G + g) * n + i] - s_lse[g]);
-      float sc = (float)((acc * invG + (LT)eps) * (LT)vnorm[(size_t)unit * n + i]);
+      float sc = (float)((acc[it] * invG + (LT)eps) * (LT)vn[it]);
       scores[(size_t)unit * n + i] = sc;
       if (hist0) atomicAdd(&s_hist[__float_as_uint(sc) >> 21], 1u);
     }

@@ -115,10 +115,16 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_hist(SelArgs a) {
   __syncthreads();
   const uint32_t* sc = reinterpret_cast<const uint32_t*>(a.scores) + (size_t)unit * a.n;
   const long long base = (long long)blockIdx.y * kSelBlock;
+  // All loads first and none under a condition (indices past the end are clamped): a load inside
+  // "if (i < n)" is followed by a wait for it, one memory round trip per score.
+  uint32_t uu[kSelPer];
+#pragma unroll
+  for (int j = 0; j < kSelPer; ++j) uu[j] = sc[min(base + j * kSelThreads + tid, a.n - 1)];
+#pragma unroll
   for (int j = 0; j < kSelPer; ++j) {
     const long long i = base + j * kSelThreads + tid;
     if (i < a.n) {
-      const uint32_t u = sc[i];
+      const uint32_t u = uu[j];
       if (P == 0) atomicAdd(&s_hist[u >> 21], 1u);
       if (P == 1 && (u >> 21) == prefix) atomicAdd(&s_hist[(u >> 10) & 2047u], 1u);
       if (P == 2 && (u >> 10) == prefix) atomicAdd(&s_hist[u & 1023u], 1u);
@@ -144,13 +150,15 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_count(SelArgs a) {
   const uint32_t* sc = reinterpret_cast<const uint32_t*>(a.scores) + (size_t)unit * a.n;
   const long long base = (long long)blockIdx.y * kSelBlock;
   uint32_t gt = 0, eq = 0;
+  uint32_t uu[kSelPer];
+#pragma unroll
+  for (int j = 0; j < kSelPer; ++j) uu[j] = sc[min(base + j * kSelThreads + tid, a.n - 1)];
+#pragma unroll
   for (int j = 0; j < kSelPer; ++j) {
     const long long i = base + j * kSelThreads + tid;
-    if (i < a.n) {
-      const uint32_t u = sc[i];
-      gt += u > T;
-      eq += u == T;
-    }
+    const uint32_t u = uu[j];
+    gt += i < a.n && u > T;
+    eq += i < a.n && u == T;
   }
   for (int o = 32; o >= 1; o >>= 1) { gt += __shfl_xor(gt, o); eq += __shfl_xor(eq, o); }
   if ((tid & 63) == 0) { atomicAdd(&s_cnt[0], gt); atomicAdd(&s_cnt[1], eq); }
@@ -228,10 +236,9 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_emit(SelArgs a) {
   uint32_t u[kSelPer];
   uint32_t eq = 0;
 #pragma unroll
-  for (int j = 0; j < kSelPer; ++j) {
-    u[j] = (i0 + j < a.n) ? sc[i0 + j] : 0u;
-    eq += (i0 + j < a.n) && u[j] == T;
-  }
+  for (int j = 0; j < kSelPer; ++j) u[j] = sc[min(i0 + j, a.n - 1)];
+#pragma unroll
+  for (int j = 0; j < kSelPer; ++j) eq += (i0 + j < a.n) && u[j] == T;
   uint32_t tot;
   uint32_t eq_before = base_eq + block_excl_scan(eq, s_tmp, &tot);
   uint32_t keepmask = 0, nk = 0;
@@ -297,12 +304,24 @@ __global__ __launch_bounds__(kSelSmallThreads) void k_sel_small(SelArgs a) {
   for (int P = 0; P < 3; ++P) {
     for (int i = tid; i < kSelBins; i += kSelSmallThreads) s_hist[i] = 0;
     __syncthreads();
-    for (int i = tid; i < n; i += kSelSmallThreads) {
-      uint32_t u;
-      if (P == 0) { u = sc[i]; s_sc[i] = u; } else { u = s_sc[i]; }
-      if (P == 0) atomicAdd(&s_hist[u >> 21], 1u);
-      if (P == 1 && (u >> 21) == prefix) atomicAdd(&s_hist[(u >> 10) & 2047u], 1u);
-      if (P == 2 && (u >> 10) == prefix) atomicAdd(&s_hist[u & 1023u], 1u);
+    // eight scores per thread at a time, all their loads issued before the first is used
+    for (int i0 = tid; i0 < n; i0 += 8 * kSelSmallThreads) {
+      uint32_t uu[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int i = min(i0 + e * kSelSmallThreads, n - 1);
+        uu[e] = P == 0 ? sc[i] : s_sc[i];
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int i = i0 + e * kSelSmallThreads;
+        if (i < n) {
+          const uint32_t u = uu[e];
+          if (P == 0) { s_sc[i] = u; atomicAdd(&s_hist[u >> 21], 1u); }
+          if (P == 1 && (u >> 21) == prefix) atomicAdd(&s_hist[(u >> 10) & 2047u], 1u);
+          if (P == 2 && (u >> 10) == prefix) atomicAdd(&s_hist[u & 1023u], 1u);
+        }
+      }
     }
     __syncthreads();
     if (tid < 64) {
