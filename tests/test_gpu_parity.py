@@ -218,6 +218,23 @@ def test_compact_bit_exact(shape, inplace):
             assert np.array_equal(vo[:, :, len(m):], v[:, :, len(m):]), name
 
 
+@pytest.mark.parametrize("n_keep", [1, 95, 96, 97, 191, 192, 193, 959, 960, 961])
+def test_compact_kept_counts_around_chunk_multiples(n_keep):
+    # in place, kept counts just below, at and just above whole chunks of destination rows
+    cfg = CONFIGS["c2"].with_(n_kv_heads=3, n_q_heads=3)
+    n = 1500
+    r = np.random.default_rng(1000 + n_keep)
+    k = r.integers(0, 2 ** 16, (1, 3, n, 128)).astype(np.uint16)
+    v = r.integers(0, 2 ** 16, (1, 3, n, 128)).astype(np.uint16)
+    idx = np.stack([np.sort(r.choice(n, n_keep, replace=False)),          # scattered
+                    np.arange(n - n_keep, n),                             # the tail, moved to the front
+                    np.arange(n_keep)])[None]                             # identity: nothing moves
+    ko, vo = P.run_compact(cfg, k, v, n, idx, inplace=True)
+    P.check_compaction(ko, vo, k, v, idx, n_keep)
+    assert np.array_equal(ko[:, 2], k[:, 2]) and np.array_equal(vo[:, 2], v[:, 2])
+    assert np.array_equal(ko[:, :, n_keep:][:, 0], k[:, :, n_keep:][:, 0])
+
+
 def test_compact_large_in_place_hazards():
     # many chunks, strongly overlapping source/destination ranges
     cfg = CONFIGS["c2"].with_(n_kv_heads=4, n_q_heads=4)
