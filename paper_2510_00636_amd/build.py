@@ -17,8 +17,11 @@ SOURCES = ["ea_host.cpp", "ea_api.hip", "ea_stats.hip", "ea_score.hip", "ea_scor
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for the device pass (the host pass warns that it
 # does not know the feature; harmless)
+# The wave-aggregation of atomics is switched off as well: it rewrites "lane 0 draws a ticket" into
+# code that reads the returned value at once, i.e. waits for the atomic where it is issued.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
 
 
 def _compile(src):

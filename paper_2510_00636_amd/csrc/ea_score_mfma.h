@@ -183,9 +183,13 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   const int ways = max(1, min(kTicketWays, a.nchunk / 8));    // at least 8 workgroups per counter
   const int way = chunk % ways;
   uint32_t* tk = a.tickets + (size_t)unit * a.ticket_stride + pass * kTicketWays + way;
+  // The counter's value is only turned into a tile number where it is used, an iteration later:
+  // any arithmetic on it here would make the wave wait for the atomic's round trip on the spot
+  // (the library is also built with the compiler's wave-aggregation of atomics switched off,
+  // which inserts exactly such an immediate use).
   auto grab = [&]() -> int {               // valid in lane 0; v_readfirstlane where it is used
     int t = 0;
-    if (lane == 0) t = (int)atomicAdd(tk, 1u) * ways + way;
+    if (lane == 0) t = (int)atomicAdd(tk, 1u);
     return t;
   };
   const int t_cur_raw = grab();
@@ -238,7 +242,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   };
 #pragma unroll
   for (int j = 0; j < NL; ++j) { kraw[j] = u32x4{0u, 0u, 0u, 0u}; vraw[j] = u32x4{0u, 0u, 0u, 0u}; }
-  int t_cur = __builtin_amdgcn_readfirstlane(t_cur_raw);
+  int t_cur = __builtin_amdgcn_readfirstlane(t_cur_raw) * ways + way;
   long long key0 = t_cur < ntiles ? tile_key(t_cur) : 0;
   if (t_cur < ntiles) {                                      // first tile: plain loads
     if constexpr (!CLAMP) {
@@ -319,7 +323,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     // ---- where the next tile comes from.  Without a next tile the loads below still run (the
     //      matrix-core phase is one straight-line block) but all lanes read the head's first
     //      16 bytes: no traffic to speak of.
-    const int t_nxt = __builtin_amdgcn_readfirstlane(t_nxt_raw);
+    const int t_nxt = __builtin_amdgcn_readfirstlane(t_nxt_raw) * ways + way;
     t_nxt_raw = grab();
     const bool has_next = t_nxt < ntiles;
     const long long nkey0 = has_next ? tile_key(t_nxt) : 0;
