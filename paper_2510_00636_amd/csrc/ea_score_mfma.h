@@ -324,7 +324,6 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     //      matrix-core phase is one straight-line block) but all lanes read the head's first
     //      16 bytes: no traffic to speak of.
     const int t_nxt = __builtin_amdgcn_readfirstlane(t_nxt_raw) * ways + way;
-    t_nxt_raw = grab();
     const bool has_next = t_nxt < ntiles;
     const long long nkey0 = has_next ? tile_key(t_nxt) : 0;
     const u32x4* kp_n = has_next ? kbase + tile_base(nkey0) * CPR : kbase;
@@ -390,6 +389,11 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
           }
         }
         // ---- vector work placed in this step
+        // The ticket after next is drawn right after the last V chunk has been consumed: the waits
+        // for the V chunks cover everything issued before them, so a ticket drawn earlier would be
+        // waited for there; drawn here it is older than every load of the next tile and has
+        // returned long before it is read.
+        if constexpr (f == NL) t_nxt_raw = grab();
         if constexpr (f < NL) {                   // V chunk f: lane lch == f keeps its row's sum
           const float ss = group_sum<CPR>(sumsq_bf16x8(vraw[f]));
           vsq = lch == f ? ss : vsq;
