@@ -88,3 +88,15 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     # n_keep == 0 is a valid no-op (returns before any launch)
     assert lib.ea_select(byref(p), VP(ok), 8, 0, None, VP(ok), 1 << 30, None) == 0
     assert lib.ea_compact(byref(p), VP(ok), VP(2 * ok), 8, 8, None, 0, VP(ok), VP(2 * ok), VP(ok), 1 << 30, None) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more exits with a message instead of pretending."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
