@@ -49,6 +49,10 @@ def parse():
                     help="HIP streams the layers are spread over (each with its own workspace); layers "
                          "are independent, so the short latency-bound kernels of one layer overlap "
                          "with the streaming kernels of another")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (all calls, one stream) in a HIP graph and time replays of it: "
+                         "the launch-latency view for short caches (the library enqueues kernels only, "
+                         "so its calls can be captured as they are)")
     return ap.parse_args()
 
 
@@ -101,7 +105,7 @@ def main():
         lay = make_layer_device(cfg, l, out_k=k0[l], out_v=v0[l], out_q=q[l])
         inv = lay["inv_freq"]
     k, v = torch.empty_like(k0), torch.empty_like(v0)
-    ns = max(1, min(a.streams, L // LB))
+    ns = 1 if a.graph else max(1, min(a.streams, L // LB))
     wss = [torch.empty(ea.workspace_bytes(p, n, w), dtype=torch.uint8, device=dev) for _ in range(ns)]
     ws = wss[0]
     streams = [torch.cuda.Stream() for _ in range(ns)] if ns > 1 else [None]      # default priority
@@ -124,6 +128,16 @@ def main():
         torch.cuda.synchronize()
         step()
         torch.cuda.synchronize()
+    if a.graph:
+        cap = torch.cuda.Stream()
+        streams = [cap]
+        graph = torch.cuda.CUDAGraph()
+        restore()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=cap):
+            step()
+        torch.cuda.synchronize()
+        step = graph.replay
     times = []
     for _ in range(a.steps):
         restore()
@@ -174,8 +188,9 @@ def main():
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
            "config": {"workload": "%s: %d layers x %d KV heads x %d tokens x d%d, Hq %d, window %d, "
-                                  "ratio %.2f (keep %d), eps %.2f, in place, %d layer(s) per call, calls spread over %d streams" %
-                                  (cfg.name, L, Hkv * B, n, d, Hq, w, a.ratio, n_keep, a.epsilon, LB, ns),
+                                  "ratio %.2f (keep %d), eps %.2f, in place, %d layer(s) per call, calls spread over %d streams%s" %
+                                  (cfg.name, L, Hkv * B, n, d, Hq, w, a.ratio, n_keep, a.epsilon, LB, ns,
+                                   ", one step replayed from a HIP graph" if a.graph else ""),
                       "pairs_per_step": pairs, "bytes_per_pair": bytes_per_pair},
            "path_hbm_frac": round(path_hbm_frac, 4),
            "stage_ms_per_layer": stages,
