@@ -200,7 +200,7 @@ def main():
     if not a.no_cpu_baseline:
         from oracle import ea_oracle as O
         from ea_inputs import widen
-        from tests.parity import to_host
+        from ea_inputs.torch_io import to_host
         invh = inv.cpu().numpy()
         done, dt = 0, 0.0
         while done < L and dt < 12.0:                      # about 10-30 s of CPU work

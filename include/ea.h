@@ -29,7 +29,9 @@
  *   - Channel pairing of the rotary embedding: rope_layout 0 pairs (c, c+d/2), 1 pairs
  *     (2c, 2c+1); pair c turns by position * inv_freq[c].
  *   - Domain: finite inputs; bf16 keys must satisfy |k| < 4096 (they are narrowed to fp16
- *     for the matrix cores, and their squares are formed in fp16 after a 2^-4 scaling).
+ *     for the matrix cores, and their squares are formed in fp16 after a 2^-4 scaling);
+ *     1 <= n <= 2^26 rows per head.  Measurement and debugging calls (they block) are in
+ *     ea_profile.h, not here.
  */
 #ifndef EA_H
 #define EA_H
@@ -107,19 +109,6 @@ ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t windo
                             const double* inv_freq, int64_t t_next, void* k, void* v, int64_t n,
                             int64_t n_cap, int64_t n_keep, float* scores_out, int32_t* idx_out,
                             void* ws, size_t ws_bytes, void* stream);
-
-/* Profiling aid, not part of the serving path: the same work as ea_compress_layer (without the
- * optional outputs), with a HIP event recorded on `stream` between stages.  It creates and
- * destroys the events, WAITS for the layer to finish, and writes the milliseconds of each
- * stage to stage_ms (HOST pointer, EA_N_STAGES floats):
- *   0 clear + rotary table + statistics   1 matrix-core operand preparation
- *   2 score pass A (K/V streaming kernel)  3 score pass B (normalise, weight by ||v||)
- *   4 selection                            5 compaction */
-#define EA_N_STAGES 6
-ea_status ea_compress_layer_timed(const ea_params* p, const void* q_win, int64_t window,
-                                  int64_t q_pos0, const double* inv_freq, int64_t t_next, void* k,
-                                  void* v, int64_t n, int64_t n_cap, int64_t n_keep, void* ws,
-                                  size_t ws_bytes, void* stream, float* stage_ms);
 
 /* Listing 1: int(n * (1 - ratio)) in IEEE double, truncated toward zero; -1 if ratio is
  * outside [0, 1] or n < 0.  Host only. */

@@ -1,4 +1,4 @@
-"""ctypes binding of include/ea.h -- same names, argument marshalling only.
+"""ctypes binding of include/ea.h and include/ea_profile.h -- same names, argument marshalling only.
 
 Tensor arguments are torch CUDA tensors (or anything with .data_ptr()); `stream` is a
 torch.cuda.Stream, a raw hipStream_t integer, or None for torch's current stream."""
@@ -56,6 +56,8 @@ def load_library():
     lib.ea_compress_layer_timed.restype = ctypes.c_int
     lib.ea_compress_layer_timed.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, SZ, VP,
                                             ctypes.POINTER(ctypes.c_float)]
+    lib.ea_debug_status.restype = ctypes.c_int
+    lib.ea_debug_status.argtypes = [P, I64, I64, VP, SZ, VP, ctypes.POINTER(ctypes.c_uint32)]
     lib.ea_n_keep.restype = I64
     lib.ea_n_keep.argtypes = [I64, ctypes.c_double]
     lib.ea_status_string.restype = ctypes.c_char_p
@@ -154,3 +156,14 @@ def compress_layer_timed(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_
                                                   _nbytes(ws), _stream(stream), ms),
            "ea_compress_layer_timed")
     return list(ms)
+
+
+STATUS_BAD_SCORE, STATUS_COMPACT_WAIT, STATUS_BAD_INDEX = 1, 2, 4
+
+
+def debug_status(p, n, window, ws, stream=None):
+    """Debugging aid (blocks): the status bits the kernels left in the workspace."""
+    word = ctypes.c_uint32(0)
+    _check(load_library().ea_debug_status(ctypes.byref(p), int(n), int(window), _ptr(ws), _nbytes(ws),
+                                          _stream(stream), ctypes.byref(word)), "ea_debug_status")
+    return int(word.value)

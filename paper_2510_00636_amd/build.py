@@ -8,7 +8,7 @@ import sys
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-CSRC = os.environ.get("EA_CSRC") or os.path.join(HERE, "csrc")
+CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libea.so")
 SOURCES = ["ea_host.cpp", "ea_api.hip", "ea_stats.hip", "ea_score.hip", "ea_score_d64.hip", "ea_score_d128.hip", "ea_score_d128b.hip",
@@ -34,12 +34,7 @@ def _compile(src):
     return obj, warn
 
 
-def build_lib(verbose=True, extra_flags=(), out=None):
-    global FLAGS, LIB, OBJ
-    if extra_flags or out:
-        FLAGS = FLAGS + list(extra_flags)
-        LIB = out or LIB
-        OBJ = os.path.join(OBJ, "variant_" + os.path.basename(LIB))
+def build_lib(verbose=True):
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 2)) as ex:
         res = list(ex.map(_compile, SOURCES))

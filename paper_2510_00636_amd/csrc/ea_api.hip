@@ -2,6 +2,7 @@
 // caller's stream.  No allocation, no synchronisation, no state besides a cached CU count.
 #include <hip/hip_runtime.h>
 
+#include "../../include/ea_profile.h"
 #include "ea_kernels.h"
 
 namespace ea {
@@ -50,7 +51,6 @@ static ea_status run_stats(const Dims& d, const void* q_win, int64_t window, int
 // The score kernel's tile counters live in words of the third histogram that the 1024-bin
 // last radix digit never touches; `hist_zeroed` says whether the caller's clearing launch has
 // covered them already.
-constexpr int kTicketSlot = 1040;
 static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                            const float* mu, const float* sigma, float* scores, uint32_t* hist0,
                            bool hist_zeroed, char* ws, const WsLayout& L, hipStream_t st,
@@ -68,21 +68,28 @@ static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t 
                              (float2*)(ws + L.part), hist + 2 * kSelBins + kTicketSlot, 3 * kSelBins,
                              st));
     if (ev) EA_TRY(hipEventRecord(ev[1], st));
-    EA_TRY(launch_finalize(d, n, ws + L.logits, 0, vnorm, ws + L.part, sp.nchunk, scores, hist0, st));
+    EA_TRY(launch_finalize(d, n, ws + L.logits, 0, vnorm, ws + L.part, sp.npart, ws + L.lse, scores,
+                           hist0, st));
   } else {
     int nchunk = 0;
     if (ev) EA_TRY(hipEventRecord(ev[0], st));
     EA_TRY(launch_score_f32(d, k, v, n, n_cap, mu, sigma, (double*)(ws + L.logits), vnorm,
                             (double2*)(ws + L.part), &nchunk, st));
     if (ev) EA_TRY(hipEventRecord(ev[1], st));
-    EA_TRY(launch_finalize(d, n, ws + L.logits, 1, vnorm, ws + L.part, nchunk, scores, hist0, st));
+    EA_TRY(launch_finalize(d, n, ws + L.logits, 1, vnorm, ws + L.part, nchunk, ws + L.lse, scores,
+                           hist0, st));
   }
   return EA_OK;
 }
 
 static size_t hist_words(const Dims& d) { return (size_t)d.units() * 3 * kSelBins; }
 static size_t flag_words(const Dims& d, int64_t n_keep) {
-  return 2 * (size_t)d.units() * ((n_keep + kCompactRows - 1) / kCompactRows + 64);
+  return 2 * (size_t)d.units() * ((n_keep + kCompactRows - 1) / kCompactRows + kCompactTicketStride);
+}
+// [a, a + bytes) and [b, b + bytes) share bytes without being the same range
+static bool partly_overlap(const void* a, const void* b, size_t bytes) {
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x != y && x < y + bytes && y < x + bytes;
 }
 
 }  // namespace ea
@@ -116,7 +123,7 @@ ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, 
   if (s != EA_OK) return s;
   if (!aligned16(k) || !aligned16(v) || !aligned16(mu) || !aligned16(sigma) || !aligned16(scores))
     return EA_ERR_INVALID_ARG;
-  if (n < 1 || n > n_cap || n > ((int64_t)1 << 30)) return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > kMaxN) return EA_ERR_INVALID_ARG;
   WsLayout L;
   if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
   return run_score(d, k, v, n, n_cap, mu, sigma, scores, nullptr, false, (char*)ws, L,
@@ -128,7 +135,7 @@ ea_status ea_select(const ea_params* p, const float* scores, int64_t n, int64_t 
   Dims d;
   ea_status s = check_params(p, &d);
   if (s != EA_OK) return s;
-  if (n < 1 || n > ((int64_t)1 << 30) || n_keep < 0 || n_keep > n) return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > kMaxN || n_keep < 0 || n_keep > n) return EA_ERR_INVALID_ARG;
   if (!aligned16(scores) || (n_keep > 0 && !aligned16(idx))) return EA_ERR_INVALID_ARG;
   WsLayout L;
   if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
@@ -148,18 +155,27 @@ ea_status ea_compact(const ea_params* p, const void* k, const void* v, int64_t n
   if (s != EA_OK) return s;
   if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
     return EA_ERR_INVALID_ARG;
-  if (n < 1 || n > n_cap || n > ((int64_t)1 << 30) || n_keep < 0 || n_keep > n)
+  if (n < 1 || n > n_cap || n > kMaxN || n_keep < 0 || n_keep > n)
     return EA_ERR_INVALID_ARG;
   if ((k_out == k) != (v_out == v)) return EA_ERR_INVALID_ARG;   // both in place or neither
   if (k_out == v || v_out == k || (k_out == v_out)) return EA_ERR_INVALID_ARG;
+  {
+    // the four tensors are either the same range (in place) or disjoint ranges
+    const size_t bytes = (size_t)d.units() * (size_t)n_cap * d.D * d.esize();
+    const void* t[4] = {k, v, k_out, v_out};
+    for (int i = 0; i < 4; ++i)
+      for (int j = i + 1; j < 4; ++j)
+        if (partly_overlap(t[i], t[j], bytes)) return EA_ERR_INVALID_ARG;
+  }
   if (n_keep > 0 && !aligned16(idx)) return EA_ERR_INVALID_ARG;
   WsLayout L;
   if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
   if (n_keep == 0) return EA_OK;
   hipStream_t st = (hipStream_t)stream;
   uint32_t* flags = (uint32_t*)((char*)ws + L.flags);
-  if (k_out == k) EA_TRY(launch_zero(flags, flag_words(d, n_keep), st));
-  EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k_out, v_out, flags, st));
+  uint32_t* status = (uint32_t*)((char*)ws + L.hist) + 2 * kSelBins + kStatusSlot;
+  EA_TRY(launch_zero(flags, k_out == k ? flag_words(d, n_keep) : 0, st, status));
+  EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k_out, v_out, flags, status, st));
   return EA_OK;
 }
 
@@ -178,7 +194,7 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
     return EA_ERR_INVALID_ARG;
   if (window < 1 + d.ddof || q_pos0 < 0 || t_next < 0) return EA_ERR_INVALID_ARG;
   if (window > kMaxWindow) return EA_ERR_UNSUPPORTED;
-  if (n < 1 || n > n_cap || n > ((int64_t)1 << 30) || n_keep < 0 || n_keep > n)
+  if (n < 1 || n > n_cap || n > kMaxN || n_keep < 0 || n_keep > n)
     return EA_ERR_INVALID_ARG;
   WsLayout L;
   if ((s = check_ws(d, n, window, ws, ws_bytes, &L)) != EA_OK) return s;
@@ -191,8 +207,8 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
   uint32_t* hist = (uint32_t*)(w + L.hist);
   uint32_t* flags = (uint32_t*)(w + L.flags);
   if (ev) EA_TRY(hipEventRecord(ev[0], st));
-  // hist .. flags are adjacent regions of ws: one clearing launch covers histograms, block
-  // counts and the compaction flags
+  // hist .. flags are adjacent regions of ws: one clearing launch covers histograms (with the
+  // status word and the tile counters in their free words), block counts and the compaction flags
   const size_t clear_words = (L.flags - L.hist) / 4 + flag_words(d, n_keep);
   if ((s = run_stats(d, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, w, L, st, hist,
                      clear_words)) != EA_OK)
@@ -206,7 +222,8 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
   if (n_keep > 0)
     EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, (uint32_t*)(w + L.blk), true, st));
   if (ev) EA_TRY(hipEventRecord(ev[5], st));
-  if (n_keep > 0) EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k, v, flags, st));
+  if (n_keep > 0)
+    EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k, v, flags, hist + 2 * kSelBins + kStatusSlot, st));
   if (ev) EA_TRY(hipEventRecord(ev[6], st));
   return EA_OK;
 }
@@ -238,6 +255,22 @@ ea_status ea_compress_layer_timed(const ea_params* p, const void* q_win, int64_t
       if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) s = EA_ERR_DEVICE;
   for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
   return s;
+}
+
+ea_status ea_debug_status(const ea_params* p, int64_t n, int64_t window, const void* ws,
+                          size_t ws_bytes, void* stream, uint32_t* status) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!status || n < 1 || n > kMaxN || window < 1 || window > kMaxWindow) return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, window, const_cast<void*>(ws), ws_bytes, &L)) != EA_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  uint32_t w = 0u;
+  EA_TRY(hipStreamSynchronize(st));
+  EA_TRY(hipMemcpy(&w, (const char*)ws + L.hist + (2 * (size_t)kSelBins + kStatusSlot) * 4, 4, hipMemcpyDeviceToHost));
+  *status = w & (EA_STATUS_BAD_SCORE | EA_STATUS_COMPACT_WAIT | EA_STATUS_BAD_INDEX);
+  return EA_OK;
 }
 
 }  // extern "C"

@@ -7,11 +7,9 @@
 
 namespace ea {
 
-#ifndef EA_NW128
-#define EA_NW128 8              // wavefronts per workgroup of the d = 128 score kernel
-#endif
-
+constexpr int kNW128 = 8;            // wavefronts per workgroup of the d = 128 score kernel
 constexpr int kMaxWindow = 4096;
+constexpr int64_t kMaxN = (int64_t)1 << 26;   // cached rows per head the launch grids cover
 constexpr int kSelBins = 2048;        // radix-select digit width: 11 + 11 + 10 bits
 constexpr int kSelBlock = 4096;       // scores per workgroup in the select passes
 constexpr int kCompactRows = 96;     // destination rows per workgroup chunk in ea_compact (not a power of two on purpose)
@@ -33,11 +31,13 @@ struct ScorePlan {
   int nfrag;    // 1 KiB fragments per (unit, pass)
   int span;     // keys per workgroup were the head split evenly (the kernel deals tiles by ticket)
   int nchunk;   // workgroups per unit = ceil(n / span)
+  int pg;       // keys per softmax partial (max, sum exp): partial j covers keys [j*pg, (j+1)*pg)
+  int npart;    // partials per query head = ceil(n / pg)
   size_t lds_bytes;
 };
 
 struct WsLayout {
-  size_t tab, mu, sigma, frags, post, logits, vnorm, part, scores, idx, hist, blk, flags, total;
+  size_t tab, mu, sigma, frags, post, logits, vnorm, part, lse, scores, idx, hist, blk, flags, total;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -45,6 +45,17 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 ea_status check_params(const ea_params* p, Dims* d);
 ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu);
 WsLayout make_ws_layout(const Dims& d, int64_t n, int64_t window);
+
+// Free words of unit 0's third radix histogram (its last digit has 1024 bins): (T, q) of the
+// selection at 1024/1025, a status word at kStatusSlot, the score kernel's tile counters from
+// kTicketSlot on.  The launch that clears the histograms clears them all.
+constexpr int kStatusSlot = 1030;
+constexpr int kTicketSlot = 1040;
+// Status bits (see ea_debug_status)
+constexpr uint32_t kStatusBadScore = 1u;      // ea_select met a negative or NaN score
+constexpr uint32_t kStatusCompactWait = 2u;   // in-place ea_compact gave up waiting: stores skipped
+constexpr uint32_t kStatusBadIndex = 4u;      // ea_compact met an idx list that is not strictly ascending in [j, n)
+constexpr int kCompactTicketStride = 64;      // words per (unit, tensor) at the head of the flag region
 
 // fragments per head of the triangular Sigma tiling, and per pass
 inline int frags_per_head(int D) { int njt = D / 32; return njt * (njt + 1); }

@@ -19,7 +19,7 @@
 namespace ea {
 
 constexpr int kCompactSpinLimit = 1 << 20;
-constexpr int kTicketStride = 64;   // words between the ticket counters of two tensors
+constexpr int kTicketStride = kCompactTicketStride;   // words between the ticket counters of two tensors
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in VGPRs
 
@@ -29,8 +29,9 @@ struct CompactArgs {
   const int32_t* idx;
   long long n_cap;
   int n, n_keep, units, nch;
-  uint32_t* flags;    // [2*units][nch] loaded flags, then [2*units][kTicketStride] ticket counters
+  uint32_t* flags;    // [2*units][kTicketStride] ticket counters, then [2*units][nch] loaded flags
   int inplace;
+  uint32_t* status;   // status word (bits kStatusCompactWait, kStatusBadIndex)
 };
 
 // First x in [0, c) for which the monotone predicate pred(x) (false ... false true ... true)
@@ -68,18 +69,19 @@ template <int RB>
 __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   constexpr int CPR = RB / 16;                 // 16-byte pieces per row
   constexpr int NLD = kCompactRows * CPR / 256;
-  __shared__ int s_c, s_lo, s_hi, s_ident;
+  __shared__ int s_c, s_lo, s_hi, s_ident, s_abort;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool control = wave == 4;
   const int ntu = 2 * a.units;
   const int tu = blockIdx.x % ntu;
-  uint32_t* flag = a.flags + (size_t)tu * a.nch;
+  uint32_t* flag = a.flags + (size_t)ntu * kTicketStride + (size_t)tu * a.nch;
   if (control && lane == 0) {
-    uint32_t* ticket = a.flags + (size_t)ntu * a.nch + (size_t)tu * kTicketStride;
+    uint32_t* ticket = a.flags + (size_t)tu * kTicketStride;
     s_c = a.inplace ? (int)atomicAdd(ticket, 1u) : (int)(blockIdx.x / ntu);
     s_lo = 0;
     s_hi = -1;
+    s_abort = 0;
   }
   __syncthreads();
   const int c = s_c;
@@ -94,6 +96,18 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   // s_ident, at the barrier before the stores.
   bool identity = false;
   if (control && a.inplace) identity = idx[j1 - 1] == j1 - 1;
+  // The control wavefront also looks at the chunk's indices themselves (two per lane, requested
+  // here, judged after the searches below): strictly ascending, idx[j] >= j, inside the tensor.
+  // A list that is not makes the in-place hazard analysis void; the status word records it.
+  int chk_cur[2] = {0, 0}, chk_prev[2] = {-1, -1};
+  if (control && tensor == 0) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int j = min(j0 + lane + 64 * t, j1 - 1);
+      chk_cur[t] = idx[j];
+      chk_prev[t] = j > 0 ? idx[j - 1] : -1;
+    }
+  }
 
   u32x4 buf[NLD];
   if (!control) {
@@ -118,6 +132,15 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
     const int hi = first_true(c, lane, [&](int x) { return idx[x * kCompactRows] >= j1; }) - 1;
     if (lane == 0) { s_lo = lo; s_hi = hi; }
   }
+  if (control && tensor == 0) {
+    bool bad = false;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int j = min(j0 + lane + 64 * t, j1 - 1);
+      bad |= chk_cur[t] <= chk_prev[t] || chk_cur[t] < j || chk_cur[t] >= a.n;
+    }
+    if (__ballot(bad) != 0ull && lane == 0) atomicOr(a.status, kStatusBadIndex);
+  }
   if (a.inplace) {
     if (control && lane == 0) s_ident = identity;
     __syncthreads();                 // every mover's loads have landed
@@ -127,14 +150,24 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
       // this XCD's L2 on every chunk).
       if (lane == 0) __hip_atomic_store(&flag[c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       // The awaited chunks hold lower tickets of the same counter, so they are running and
-      // will publish; the spin bound only keeps a malformed idx from turning into a hang.
-      for (int cc = s_lo + lane; cc <= s_hi; cc += 64)
-        for (int spin = 0; spin < kCompactSpinLimit &&
-             __hip_atomic_load(&flag[cc], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u; ++spin)
+      // will publish; the spin bound only keeps a malformed idx from turning into a hang.  A wait
+      // that runs out never stores past an unseen flag: the chunk's stores are skipped and the
+      // workspace's status word says so (ea_debug_status).
+      bool seen = true;
+      for (int cc = s_lo + lane; cc <= s_hi; cc += 64) {
+        int spin = 0;
+        while (__hip_atomic_load(&flag[cc], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+          if (++spin >= kCompactSpinLimit) { seen = false; break; }
           __builtin_amdgcn_s_sleep(4);
+        }
+      }
+      if (!seen) {
+        s_abort = 1;
+        atomicOr(a.status, kStatusCompactWait);
+      }
     }
     __syncthreads();                 // stores are issued only after every awaited flag was seen
-    identity = s_ident != 0;
+    identity = s_ident != 0 || s_abort != 0;
   }
   if (!control && !identity) {
 #pragma unroll
@@ -147,7 +180,7 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
 
 hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                           const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
-                          uint32_t* flags, hipStream_t st) {
+                          uint32_t* flags, uint32_t* status, hipStream_t st) {
   CompactArgs a;
   a.n = (int)n;
   a.src[0] = (const u32x4*)k;
@@ -160,6 +193,7 @@ hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n
   a.units = d.units();
   a.nch = (int)((n_keep + kCompactRows - 1) / kCompactRows);
   a.flags = flags;
+  a.status = status;
   a.inplace = (k_out == k && v_out == v) ? 1 : 0;
   const int rb = d.D * d.esize();
   const unsigned grid = 2u * a.units * a.nch;

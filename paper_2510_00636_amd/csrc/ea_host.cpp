@@ -44,7 +44,7 @@ ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
   const int inst64[] = {1, 2, 4, 8}, inst128[] = {1, 2, 3, 4, 5}, inst256[] = {1};
   const int* inst = d.D == 64 ? inst64 : d.D == 128 ? inst128 : inst256;
   const int ninst = d.D == 64 ? 4 : d.D == 128 ? 5 : 1;
-  s.NW = d.D == 256 ? 4 : d.D == 128 ? EA_NW128 : 8;
+  s.NW = d.D == 256 ? 4 : d.D == 128 ? kNW128 : 8;
   const size_t stage = (size_t)s.NW * 16 * d.D * 2;
   int ghmax = 1;
   for (int i = 0; i < ninst; ++i)
@@ -65,6 +65,8 @@ ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
   if (span < tile) span = tile;
   s.span = (int)span;
   s.nchunk = (int)((n + span - 1) / span);
+  s.pg = 32;
+  s.npart = (int)((n + s.pg - 1) / s.pg);
   return s;
 }
 
@@ -85,14 +87,18 @@ WsLayout make_ws_layout(const Dims& d, int64_t n, int64_t window) {
   w.post = take(qh * 2 * sizeof(float));
   w.logits = take(qh * (size_t)n * 8);          // fp32 logits (bf16 path) or fp64 (fp32 path)
   w.vnorm = take(un * (size_t)n * sizeof(float));
-  w.part = take(qh * 1024 * 16);                // (max, sum) per workgroup, float2 or double2
+  // (max, sum exp) partials: float2 per fixed block of keys (bf16 path), double2 per chunk (fp32 path)
+  size_t part_bytes = qh * (size_t)sp.npart * 8;
+  if (part_bytes < qh * 1024 * 16) part_bytes = qh * 1024 * 16;
+  w.part = take(part_bytes);
+  w.lse = take(qh * sizeof(double));
   w.scores = take(un * (size_t)n * sizeof(float));
   w.idx = take(un * (size_t)n * sizeof(int32_t));
   w.hist = take(un * 3 * kSelBins * sizeof(uint32_t) + 256);
   size_t nblk = ((size_t)n + kSelBlock - 1) / kSelBlock;
   w.blk = take(un * nblk * 2 * sizeof(uint32_t));
   size_t nch = ((size_t)n + kCompactRows - 1) / kCompactRows;
-  w.flags = take(2 * un * (nch + 64) * sizeof(uint32_t));   // flags + ticket counters
+  w.flags = take(2 * un * (nch + kCompactTicketStride) * sizeof(uint32_t));   // ticket counters, then flags
   w.total = o;
   return w;
 }
@@ -104,7 +110,7 @@ extern "C" {
 size_t ea_workspace_bytes(const ea_params* p, int64_t n, int64_t window) {
   ea::Dims d;
   if (ea::check_params(p, &d) != EA_OK) return 0;
-  if (n < 1 || n > (int64_t)1 << 30 || window < 1 || window > ea::kMaxWindow) return 0;
+  if (n < 1 || n > ea::kMaxN || window < 1 || window > ea::kMaxWindow) return 0;
   return ea::make_ws_layout(d, n, window).total;
 }
 

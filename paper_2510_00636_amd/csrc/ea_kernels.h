@@ -24,8 +24,10 @@ hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t
                             const float* mu, const float* sigma, double* logits, float* vnorm,
                             double2* part, int* nchunk_out, hipStream_t st);
 // scores = (mean_g exp(l_g - lse_g) + eps) * vnorm; hist0 (nullable): first radix digit
+// part: npart (max, sum exp) pairs per query head, each over a fixed block of keys; lse: scratch of
+// one LT per query head (used when a head has too many partials to reduce inside pass B)
 hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
-                           const float* vnorm, const void* part, int nchunk, float* scores,
+                           const float* vnorm, const void* part, int npart, void* lse, float* scores,
                            uint32_t* hist0, hipStream_t st);
 
 // ea_select.hip
@@ -35,13 +37,28 @@ constexpr int64_t kSelSmallMax = 32768;
 inline bool select_in_one_launch(int64_t n) { return n <= kSelSmallMax; }
 hipError_t launch_select(const Dims& d, const float* scores, int64_t n, int64_t n_keep, int32_t* idx,
                          uint32_t* hist, uint32_t* blk, bool hist0_done, hipStream_t st);
-hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st);
+hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st, uint32_t* extra = nullptr);
 
 // ea_compact.hip
 hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                           const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
-                          uint32_t* flags, hipStream_t st);
+                          uint32_t* flags, uint32_t* status, hipStream_t st);
 
 int device_num_cu();
+
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) once per (kernel, device) instead of on every
+// launch: a static instance of this sits next to each launch of a kernel that needs more than
+// 64 KiB of LDS.  Racing first calls at worst set the attribute twice.
+struct LdsOptIn {
+  size_t have[64] = {0};
+  hipError_t ensure(const void* kern, size_t bytes) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+    if (dev >= 0 && have[dev] >= bytes) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && dev >= 0) have[dev] = bytes;
+    return e;
+  }
+};
 
 }  // namespace ea

@@ -27,6 +27,7 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
   a.G = d.G;
   a.passes = sp.passes;
   a.nchunk = sp.nchunk;
+  a.npart = sp.npart;
   a.units = d.units();
   a.nfrag = sp.nfrag;
   a.tickets = tickets;
@@ -142,8 +143,8 @@ hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t
 #define EA_F32(DD)                                                                              \
   if (d.D == DD) {                                                                              \
     auto kern = k_score_f32<DD>;                                                                \
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                     \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   \
+    static LdsOptIn opt;                                                                        \
+    hipError_t e = opt.ensure(reinterpret_cast<const void*>(kern), lds);                        \
     if (e != hipSuccess) return e;                                                              \
     kern<<<grid, 256, lds, st>>>((const float*)k, (const float*)v, n, n_cap, mu, sigma, d.G,    \
                                  d.units(), (int)span, nchunk, logits, vnorm, part);            \
@@ -157,9 +158,14 @@ hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t
 }
 
 // ---------------------------------------------------------------------------------------
-// Pass B.  One workgroup = 1024 keys of one unit.  LT is the logit type (float: bf16 caches,
-// double: fp32 caches).  With hist0 != nullptr the first radix-select digit (top 11 bits of
-// the score's bit pattern) is histogrammed on the way out.
+// Pass B.  One workgroup = `rounds` x 1024 keys of one unit.  LT is the logit type (float: bf16
+// caches, double: fp32 caches).  With hist0 != nullptr the first radix-select digit (top 11
+// bits of the score's bit pattern) is histogrammed on the way out.
+//
+// The (max, sum exp) partials of pass A belong to fixed blocks of keys (partial j of a head
+// covers the same keys in every run) and are combined here in index order, so the log-sum-exp,
+// and with it every score, comes out bit-identical from run to run however pass A's tiles were
+// dealt to workgroups.
 template <typename LT>
 struct LT2;
 template <>
@@ -173,65 +179,104 @@ __device__ __forceinline__ float ea_log(float x) { return logf(x); }
 __device__ __forceinline__ double ea_log(double x) { return log(x); }
 
 template <typename LT>
+__device__ __forceinline__ void merge_lt(LT& m, LT& s, LT m2, LT s2) {
+  LT mn = m > m2 ? m : m2;
+  if (mn == -INFINITY) { s = 0; m = mn; }
+  else { s = s * ea_exp(m - mn) + s2 * ea_exp(m2 - mn); m = mn; }
+}
+
+// log-sum-exp of one head from its npart partials, by one wavefront: lane l takes partials
+// l, l + 64, ... in increasing order, then a fixed butterfly over the lanes.
+template <typename LT>
+__device__ __forceinline__ LT wave_lse(const typename LT2<LT>::type* __restrict__ p, int npart, int lane) {
+  LT m = -INFINITY, s = 0;
+  for (int c = lane; c < npart; c += 64) merge_lt<LT>(m, s, p[c].x, p[c].y);
+  for (int o = 32; o >= 1; o >>= 1) {
+    LT m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
+    merge_lt<LT>(m, s, m2, s2);
+  }
+  return m + ea_log(s);
+}
+
+// Heads with very many partials: one workgroup per query head reduces them once, ahead of
+// pass B (otherwise every workgroup of pass B would walk the whole list).
+template <typename LT>
+__global__ __launch_bounds__(256) void k_lse(const typename LT2<LT>::type* __restrict__ part, int npart,
+                                             LT* __restrict__ lse) {
+  __shared__ LT s_m[4], s_s[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const typename LT2<LT>::type* p = part + (size_t)blockIdx.x * npart;
+  LT m = -INFINITY, s = 0;
+  for (int c = tid; c < npart; c += 256) merge_lt<LT>(m, s, p[c].x, p[c].y);
+  for (int o = 32; o >= 1; o >>= 1) {
+    LT m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
+    merge_lt<LT>(m, s, m2, s2);
+  }
+  if (lane == 0) { s_m[wave] = m; s_s[wave] = s; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 4; ++w) merge_lt<LT>(m, s, s_m[w], s_s[w]);
+    lse[blockIdx.x] = m + ea_log(s);
+  }
+}
+
+template <typename LT>
 __global__ __launch_bounds__(256) void k_finalize(const LT* __restrict__ logits,
                                                   const float* __restrict__ vnorm,
                                                   const typename LT2<LT>::type* __restrict__ part,
-                                                  int G, int nchunk, long long n, float eps,
+                                                  const LT* __restrict__ lse_in, int G, int npart,
+                                                  long long n, float eps, int units, int rounds,
                                                   float* __restrict__ scores,
                                                   uint32_t* __restrict__ hist0) {
   __shared__ LT s_lse[64];
   __shared__ uint32_t s_hist[kSelBins];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int unit = blockIdx.x;
+  const int unit = blockIdx.x % units;
+  const long long blk = blockIdx.x / units;
   if (hist0)
     for (int i = tid; i < kSelBins; i += 256) s_hist[i] = 0;
   for (int g = wave; g < G; g += 4) {
-    const typename LT2<LT>::type* p = part + ((size_t)unit * G + g) * nchunk;
-    LT m = -INFINITY, s = 0;
-    for (int c = lane; c < nchunk; c += 64) {
-      LT m2 = p[c].x, s2 = p[c].y;
-      LT mn = m > m2 ? m : m2;
-      if (mn == -INFINITY) { s = 0; m = mn; }
-      else { s = s * ea_exp(m - mn) + s2 * ea_exp(m2 - mn); m = mn; }
-    }
-    for (int o = 32; o >= 1; o >>= 1) {
-      LT m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
-      LT mn = m > m2 ? m : m2;
-      if (mn == -INFINITY) { s = 0; m = mn; }
-      else { s = s * ea_exp(m - mn) + s2 * ea_exp(m2 - mn); m = mn; }
-    }
-    if (lane == 0) s_lse[g] = m + ea_log(s);
+    const LT v = lse_in ? lse_in[(size_t)unit * G + g]
+                        : wave_lse<LT>(part + ((size_t)unit * G + g) * npart, npart, lane);
+    if (lane == 0) s_lse[g] = v;
   }
   __syncthreads();
-  const long long base = (long long)blockIdx.y * 1024;
   const LT invG = (LT)1 / (LT)G;
-  // The four keys of a thread go through the heads together and no load sits under a condition
-  // (indices past the end are clamped): loads inside "if (i < n)" come back one at a time.
-  long long ic[4];
-  float vn[4];
-  LT acc[4];
+  for (int rd = 0; rd < rounds; ++rd) {
+    const long long base = (blk * rounds + rd) * 1024;
+    if (base >= n) break;
+    // The four keys of a thread go through the heads together and no load sits under a condition
+    // (indices past the end are clamped): loads inside "if (i < n)" come back one at a time.
+    long long ic[4];
+    float vn[4];
+    LT acc[4];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    ic[it] = min(base + it * 256 + tid, n - 1);
-    vn[it] = vnorm[(size_t)unit * n + ic[it]];
-    acc[it] = 0;
-  }
-  for (int g = 0; g < G; ++g) {
-    const LT* lp = logits + ((size_t)unit * G + g) * n;
-    const LT lse = s_lse[g];
-    LT lv[4];
+    for (int it = 0; it < 4; ++it) {
+      ic[it] = min(base + it * 256 + tid, n - 1);
+      vn[it] = vnorm[(size_t)unit * n + ic[it]];
+      acc[it] = 0;
+    }
+    for (int g = 0; g < G; ++g) {
+      const LT* lp = logits + ((size_t)unit * G + g) * n;
+      const LT lse = s_lse[g];
+      LT lv[4];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) lv[it] = lp[ic[it]];
+      for (int it = 0; it < 4; ++it) lv[it] = lp[ic[it]];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) acc[it] += ea_exp(lv[it] - lse);
-  }
+      for (int it = 0; it < 4; ++it) acc[it] += ea_exp(lv[it] - lse);
+    }
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const long long i = base + it * 256 + tid;
-    if (i < n) {
-      float sc = (float)((acc[it] * invG + (LT)eps) * (LT)vn[it]);
-      scores[(size_t)unit * n + i] = sc;
-      if (hist0) atomicAdd(&s_hist[__float_as_uint(sc) >> 21], 1u);
+    for (int it = 0; it < 4; ++it) {
+      const long long i = base + it * 256 + tid;
+      if (i < n) {
+        float sc = (float)((acc[it] * invG + (LT)eps) * (LT)vn[it]);
+        scores[(size_t)unit * n + i] = sc;
+        if (hist0) {
+          atomicAdd(&s_hist[__float_as_uint(sc) >> 21], 1u);
+          if (__float_as_uint(sc) > 0x7f800000u)      // NaN (non-finite inputs): see ea_debug_status
+            atomicOr(hist0 + 2 * kSelBins + kStatusSlot, kStatusBadScore);
+        }
+      }
     }
   }
   if (hist0) {
@@ -243,16 +288,26 @@ __global__ __launch_bounds__(256) void k_finalize(const LT* __restrict__ logits,
   }
 }
 
+constexpr int kLseInlineMax = 4096;   // more partials per head than this: reduce them in k_lse first
+
 hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
-                           const float* vnorm, const void* part, int nchunk, float* scores,
+                           const float* vnorm, const void* part, int npart, void* lse, float* scores,
                            uint32_t* hist0, hipStream_t st) {
-  dim3 grid(d.units(), (unsigned)((n + 1023) / 1024));
-  if (logits_f64)
-    k_finalize<double><<<grid, 256, 0, st>>>((const double*)logits, vnorm, (const double2*)part, d.G,
-                                             nchunk, n, d.eps, scores, hist0);
-  else
-    k_finalize<float><<<grid, 256, 0, st>>>((const float*)logits, vnorm, (const float2*)part, d.G,
-                                            nchunk, n, d.eps, scores, hist0);
+  const int rounds = n > 32768 ? 4 : 1;
+  const int64_t nblk = (n + 1024 * rounds - 1) / (1024 * rounds);
+  const unsigned grid = (unsigned)(nblk * d.units());
+  const bool pre = npart > kLseInlineMax;
+  if (logits_f64) {
+    if (pre) k_lse<double><<<d.qheads(), 256, 0, st>>>((const double2*)part, npart, (double*)lse);
+    k_finalize<double><<<grid, 256, 0, st>>>((const double*)logits, vnorm, (const double2*)part,
+                                             pre ? (const double*)lse : nullptr, d.G, npart, n, d.eps,
+                                             d.units(), rounds, scores, hist0);
+  } else {
+    if (pre) k_lse<float><<<d.qheads(), 256, 0, st>>>((const float2*)part, npart, (float*)lse);
+    k_finalize<float><<<grid, 256, 0, st>>>((const float*)logits, vnorm, (const float2*)part,
+                                            pre ? (const float*)lse : nullptr, d.G, npart, n, d.eps,
+                                            d.units(), rounds, scores, hist0);
+  }
   return hipGetLastError();
 }
 

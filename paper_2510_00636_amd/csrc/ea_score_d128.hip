@@ -7,9 +7,9 @@ hipError_t launch_score_mfma_d128(const ScoreArgs& a, const ScorePlan& sp, hipSt
 #define EA_CASE(GG, WW)                 \
   if (sp.GH == GG && sp.NW == WW)     \
   return a.n < 32 ? launch_one<128, GG, WW, true>(a, sp, st) : launch_one<128, GG, WW, false>(a, sp, st)
-  EA_CASE(1, EA_NW128);
-  EA_CASE(2, EA_NW128);
-  EA_CASE(3, EA_NW128);
+  EA_CASE(1, kNW128);
+  EA_CASE(2, kNW128);
+  EA_CASE(3, kNW128);
 #undef EA_CASE
   return hipErrorInvalidValue;
 }

@@ -8,12 +8,9 @@
 
 #include "ea_kernels.h"
 
-#ifndef EA_FRAG_PREFETCH
-#define EA_FRAG_PREFETCH 4        // LDS fragments in flight ahead of the MFMA that consumes them
-#endif
-
 namespace ea {
 
+constexpr int kFragPrefetch = 4;  // LDS fragments in flight ahead of the MFMA that consumes them
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
@@ -35,6 +32,7 @@ struct ScoreArgs {
   float* vnorm;
   float2* part;
   int G, passes, nchunk, units, nfrag;     // nchunk: workgroups per (unit, pass)
+  int npart;              // (max, sum exp) partials per query head: partial j covers keys [32j, 32j+32)
   uint32_t* tickets;      // tickets + unit * ticket_stride + pass * kTicketWays + way: tile counters, zero at launch
   int ticket_stride;
 };
@@ -91,12 +89,29 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
-// merge two online-softmax states (m, s): value = s * exp(m)
-__device__ __forceinline__ void merge_ms(float& m, float& s, float m2, float s2) {
-  float mn = fmaxf(m, m2);
-  if (mn == -INFINITY) { s = 0.f; m = mn; return; }
-  s = s * __expf(m - mn) + s2 * __expf(m2 - mn);
-  m = mn;
+// Max / sum over the first 32 lanes of the wavefront as a wave-uniform value: butterfly inside
+// each row of 16 lanes, then the two row totals are read out with v_readlane (no trip through
+// LDS, no wait).  The callers hold the same data in lanes l and l + 32.
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float x) {
+  int y = __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, 0xf, 0xf, false);
+  return fmaxf(x, __int_as_float(y));
+}
+__device__ __forceinline__ float max_lanes32(float x) {
+  x = dpp_max<0xB1>(x);
+  x = dpp_max<0x4E>(x);
+  x = dpp_max<0x141>(x);
+  x = dpp_max<0x140>(x);
+  return fmaxf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0)),
+               __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16)));
+}
+__device__ __forceinline__ float sum_lanes32(float x) {
+  x = dpp_add<0xB1>(x);
+  x = dpp_add<0x4E>(x);
+  x = dpp_add<0x141>(x);
+  x = dpp_add<0x140>(x);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0)) +
+         __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
 }
 
 // compile-time loop: f(std::integral_constant<int, 0>) ... f(<N-1>), so that every register
@@ -157,7 +172,6 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: lives in an SGPR
   u32x4* stg = smem + NFRAG * 64 + wave * (16 * CPR);
-  float2* red = reinterpret_cast<float2*>(smem + NFRAG * 64 + NW * (16 * CPR));
 
   // Workgroups are dealt to the chip's 8 dies round-robin by index; the transposition below
   // gives every unit workgroups on all of them.  Together with the tile tickets further down it
@@ -224,10 +238,6 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   const u32x4* kbase = a.k + (size_t)unit * a.n_cap * CPR;
   const u32x4* vbase = a.v + (size_t)unit * a.n_cap * CPR;
 
-  float m_run[GH], s_run[GH];
-#pragma unroll
-  for (int g = 0; g < GH; ++g) { m_run[g] = -INFINITY; s_run[g] = 0.f; }
-
   // One 32-key tile = NL wave-wide 16-byte loads per tensor, addressed as (uniform tile base)
   // + lane*16 + j*1024 so that the address arithmetic stays on the scalar unit.  K and V are
   // read once: the loads carry the non-temporal hint, which keeps them from pushing the logits
@@ -274,9 +284,9 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   // Results of a tile are stored one iteration later, right after the staging of the next
   // tile: global stores share the in-order counter of the loads, and stores issued while
   // loads are pending make every later wait for a load also wait for the store.
-  float lg_prev[GH], vsq_prev = 0.f;
+  float lg_prev[GH], mt_prev[GH], st_prev[GH], vsq_prev = 0.f;
 #pragma unroll
-  for (int g = 0; g < GH; ++g) lg_prev[g] = 0.f;
+  for (int g = 0; g < GH; ++g) { lg_prev[g] = 0.f; mt_prev[g] = 0.f; st_prev[g] = 0.f; }
   long long key_prev = 0;
   bool have_prev = false;
   auto store_prev = [&]() {
@@ -286,6 +296,14 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 #pragma unroll
       for (int g = 0; g < GH; ++g)
         if (g0 + g < a.G) a.logits[((size_t)unit * a.G + g0 + g) * a.n + key] = lg_prev[g];
+    }
+    // the tile's (max, sum exp) goes to the slot of its key block: whichever wave scored the
+    // tile, the finalize pass finds the same numbers in the same places
+    if (lane == 0) {
+#pragma unroll
+      for (int g = 0; g < GH; ++g)
+        if (g0 + g < a.G)
+          a.part[((size_t)unit * a.G + g0 + g) * a.npart + (key_prev >> 5)] = make_float2(mt_prev[g], st_prev[g]);
     }
     if (do_v) {
       const long long row = b0 + lch * RPL + lrow;
@@ -348,7 +366,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     {
       // (the five-head instance prefetches one fragment less: with four it spills, and a kernel that
       // needs scratch memory pays for it at every launch)
-      constexpr int NX = 2 * NKS, NS = NX + GH * NF, NT = GH * NJT, PD = GH >= 5 ? 3 : EA_FRAG_PREFETCH;
+      constexpr int NX = 2 * NKS, NS = NX + GH * NF, NT = GH * NJT, PD = GH >= 5 ? 3 : kFragPrefetch;
       half8 fb[PD + 1];
       floatx16 ex, accb[3];
       static_for<PD>([&](auto i_) {
@@ -433,11 +451,9 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
       float lg = partial[g] * pq[g] + lin[g];
       lg = sum_halves(lg);
       lg_prev[g] = lg;
-      if (valid && g0 + g < a.G) {
-        float mn = fmaxf(m_run[g], lg);
-        s_run[g] = s_run[g] * __expf(m_run[g] - mn) + __expf(lg - mn);
-        m_run[g] = mn;
-      }
+      const float mt = max_lanes32(valid ? lg : -INFINITY);      // a tile always holds a valid key
+      mt_prev[g] = mt;
+      st_prev[g] = sum_lanes32(valid ? __expf(lg - mt) : 0.f);
     }
     vsq_prev = vsq;
     key_prev = key0;
@@ -446,33 +462,13 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   }
   if (have_prev) store_prev();
 
-  // ---- (max, sum) of this workgroup's keys, per head
-#pragma unroll
-  for (int g = 0; g < GH; ++g) {
-    float m = m_run[g], s = s_run[g];
-#pragma unroll
-    for (int o = 16; o >= 1; o >>= 1) {
-      float m2 = __shfl_xor(m, o), s2 = __shfl_xor(s, o);
-      merge_ms(m, s, m2, s2);
-    }
-    if (lane == 0) red[wave * GH + g] = make_float2(m, s);
-  }
-  __syncthreads();
-  if (tid < GH && g0 + tid < a.G) {
-    float m = -INFINITY, s = 0.f;
-    for (int w = 0; w < NW; ++w) {
-      float2 o = red[w * GH + tid];
-      merge_ms(m, s, o.x, o.y);
-    }
-    a.part[((size_t)unit * a.G + g0 + tid) * a.nchunk + chunk] = make_float2(m, s);
-  }
 }
 
 template <int D, int GH, int NW, bool CLAMP>
 inline hipError_t launch_one(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st) {
   auto kern = k_score_mfma<D, GH, NW, CLAMP>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)sp.lds_bytes);
+  static LdsOptIn opt;                    // one per kernel instance
+  hipError_t e = opt.ensure(reinterpret_cast<const void*>(kern), sp.lds_bytes);
   if (e != hipSuccess) return e;
   int grid = a.units * a.nchunk * a.passes;
   kern<<<grid, NW * 64, sp.lds_bytes, st>>>(a);

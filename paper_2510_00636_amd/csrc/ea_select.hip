@@ -15,14 +15,16 @@ namespace ea {
 constexpr int kSelThreads = 256;
 constexpr int kSelPer = kSelBlock / kSelThreads;   // 16 consecutive scores per thread
 
-__global__ void k_zero(uint32_t* p, size_t count) {
+// zeroes p[0, count) and, if given, the single word *extra
+__global__ void k_zero(uint32_t* p, size_t count, uint32_t* extra) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < count) p[i] = 0;
+  if (extra && i == 0) *extra = 0;
 }
 
-hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st) {
-  if (count == 0) return hipSuccess;
-  k_zero<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(p, count);
+hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st, uint32_t* extra) {
+  if (count == 0 && !extra) return hipSuccess;
+  k_zero<<<(unsigned)((count + 255) / 256 + (count == 0)), 256, 0, st>>>(p, count, extra);
   return hipGetLastError();
 }
 
@@ -125,7 +127,12 @@ __global__ __launch_bounds__(kSelThreads) void k_sel_hist(SelArgs a) {
     const long long i = base + j * kSelThreads + tid;
     if (i < a.n) {
       const uint32_t u = uu[j];
-      if (P == 0) atomicAdd(&s_hist[u >> 21], 1u);
+      if (P == 0) {
+        atomicAdd(&s_hist[u >> 21], 1u);
+        // outside the domain (negative or NaN): the order of bit patterns is not the order of
+        // values there; the selection still completes, the status word records it
+        if (u > 0x7f800000u) atomicOr(a.hist + 2 * kSelBins + kStatusSlot, kStatusBadScore);
+      }
       if (P == 1 && (u >> 21) == prefix) atomicAdd(&s_hist[(u >> 10) & 2047u], 1u);
       if (P == 2 && (u >> 10) == prefix) atomicAdd(&s_hist[u & 1023u], 1u);
     }
@@ -317,7 +324,11 @@ __global__ __launch_bounds__(kSelSmallThreads) void k_sel_small(SelArgs a) {
         const int i = i0 + e * kSelSmallThreads;
         if (i < n) {
           const uint32_t u = uu[e];
-          if (P == 0) { s_sc[i] = u; atomicAdd(&s_hist[u >> 21], 1u); }
+          if (P == 0) {
+            s_sc[i] = u;
+            atomicAdd(&s_hist[u >> 21], 1u);
+            if (u > 0x7f800000u) atomicOr(a.hist + 2 * kSelBins + kStatusSlot, kStatusBadScore);
+          }
           if (P == 1 && (u >> 21) == prefix) atomicAdd(&s_hist[(u >> 10) & 2047u], 1u);
           if (P == 2 && (u >> 10) == prefix) atomicAdd(&s_hist[u & 1023u], 1u);
         }
@@ -373,8 +384,9 @@ hipError_t launch_select(const Dims& d, const float* scores, int64_t n, int64_t 
   a.nblk = (int)((n + kSelBlock - 1) / kSelBlock);
   if (select_in_one_launch(n)) {
     const size_t lds = ((size_t)kSelBins + (size_t)n + 4) * sizeof(uint32_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_sel_small),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static LdsOptIn opt;
+    hipError_t e = opt.ensure(reinterpret_cast<const void*>(k_sel_small),
+                              ((size_t)kSelBins + (size_t)kSelSmallMax + 4) * sizeof(uint32_t));
     if (e != hipSuccess) return e;
     k_sel_small<<<d.units(), kSelSmallThreads, lds, st>>>(a);
     return hipGetLastError();

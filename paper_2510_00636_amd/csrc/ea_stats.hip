@@ -451,8 +451,8 @@ static hipError_t launch_stats_one(const Dims& d, const void* q_win, int w, cons
                                    float* mu, float* sigma, hipStream_t st) {
   auto kern = k_stats<D, BF16>;
   const size_t lds = (size_t)(kStatsWC * D + 6 * D) * sizeof(float);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static LdsOptIn opt;                    // one per kernel instance
+  hipError_t e = opt.ensure(reinterpret_cast<const void*>(kern), lds);
   if (e != hipSuccess) return e;
   dim3 grid(d.qheads(), D / 32);
   kern<<<grid, 256, lds, st>>>(q_win, w, d.rope_layout, d.ddof, tab, mu, sigma);

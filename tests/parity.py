@@ -3,21 +3,8 @@ the Python binding, download, and compare with the fp64 oracle."""
 import numpy as np
 
 import paper_2510_00636_amd as ea
+from ea_inputs.torch_io import to_dev, to_host          # noqa: F401  (re-exported for the tests)
 from oracle import ea_oracle as O
-
-
-def to_dev(a):
-    import torch
-    if a.dtype == np.uint16:
-        return torch.from_numpy(a.view(np.int16).copy()).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
-
-
-def to_host(t):
-    import torch
-    if t.dtype == torch.bfloat16:
-        return t.view(torch.int16).cpu().numpy().view(np.uint16)
-    return t.cpu().numpy()
 
 
 def params_for(cfg, epsilon=None, rope_layout=0, q_is_rotated=1, ddof=0, T=None):
@@ -158,11 +145,18 @@ def check_idx_exact_given_scores(idx, gpu_scores32, n_keep):
     assert np.array_equal(idx.astype(np.int64), ref)
 
 
-def check_compaction(k_after, v_after, k_before, v_before, idx, n_keep):
-    """Bytes bit-exact given the indices; rows >= n_keep untouched."""
+def check_compaction(k_after, v_after, k_before, v_before, idx, n_keep, rest="same"):
+    """Bytes bit-exact given the indices.  Rows >= n_keep: rest="same" -- what they were before
+    (in place); rest="zero" -- still the zeros the output buffers were created with (out of
+    place); rest=None -- not looked at."""
     i = idx.astype(np.int64)[..., None]
     assert np.array_equal(k_after[:, :, :n_keep], np.take_along_axis(k_before, i, axis=2))
     assert np.array_equal(v_after[:, :, :n_keep], np.take_along_axis(v_before, i, axis=2))
+    if rest == "same":
+        assert np.array_equal(k_after[:, :, n_keep:], k_before[:, :, n_keep:]), "K rows past n_keep changed"
+        assert np.array_equal(v_after[:, :, n_keep:], v_before[:, :, n_keep:]), "V rows past n_keep changed"
+    elif rest == "zero":
+        assert not k_after[:, :, n_keep:].any() and not v_after[:, :, n_keep:].any()
 
 
 def check_layer(cfg, lay, got, ref, n_keep, tol):

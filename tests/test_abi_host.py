@@ -21,10 +21,12 @@ def lib():
 
 
 def test_exports_every_declared_symbol(lib):
-    hdr = open(os.path.join(ROOT, "include", "ea.h")).read()
-    names = set(re.findall(r"\b(ea_[a-z_]+)\s*\(", hdr))
-    assert {"ea_workspace_bytes", "ea_query_stats", "ea_score", "ea_select", "ea_compact",
-            "ea_compress_layer", "ea_n_keep", "ea_status_string"} <= names
+    hdr = "".join(open(os.path.join(ROOT, "include", f)).read()
+                  for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
+    names = set(re.findall(r"\b(ea_[a-z_0-9]+)\s*\(", hdr))
+    assert {"ea_workspace_bytes", "ea_query_stats", "ea_score", "ea_select",
+            "ea_compact", "ea_compress_layer", "ea_n_keep", "ea_status_string",
+            "ea_compress_layer_timed", "ea_debug_status"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
@@ -85,6 +87,12 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     # compaction: one tensor in place and the other not; aliasing outputs
     assert lib.ea_compact(byref(p), VP(ok), VP(2 * ok), 8, 8, VP(ok), 4, VP(ok), VP(3 * ok), VP(ok), 1 << 30, None) == 1
     assert lib.ea_compact(byref(p), VP(ok), VP(2 * ok), 8, 8, VP(ok), 4, VP(3 * ok), VP(3 * ok), VP(ok), 1 << 30, None) == 1
+    # compaction: outputs that overlap the inputs without being the same range
+    assert lib.ea_compact(byref(p), VP(ok), VP(2 * ok), 8, 8, VP(ok), 4, VP(ok + 256), VP(3 * ok), VP(ok), 1 << 30, None) == 1
+    assert lib.ea_compact(byref(p), VP(ok), VP(2 * ok), 8, 8, VP(ok), 4, VP(4 * ok), VP(2 * ok + 512), VP(ok), 1 << 30, None) == 1
+    # more rows per head than the launch grids cover
+    assert lib.ea_select(byref(p), VP(ok), (1 << 26) + 1, 4, VP(ok), VP(ok), 1 << 40, None) == 1
+    assert ea.workspace_bytes(p, (1 << 26) + 1, 64) == 0
     # n_keep == 0 is a valid no-op (returns before any launch)
     assert lib.ea_select(byref(p), VP(ok), 8, 0, None, VP(ok), 1 << 30, None) == 0
     assert lib.ea_compact(byref(p), VP(ok), VP(2 * ok), 8, 8, None, 0, VP(ok), VP(2 * ok), VP(ok), 1 << 30, None) == 0
