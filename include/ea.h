@@ -94,6 +94,19 @@ ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, 
 ea_status ea_select(const ea_params* p, const float* scores, int64_t n, int64_t n_keep,
                     int32_t* idx, void* ws, size_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): ea_select with its scratch (radix
+ * histograms, per-block counts; about 1.6 MiB) in a static device array inside the library
+ * instead of `ws`.  Same inputs, outputs and result as ea_select.  It allocates nothing and
+ * calls no allocating routine.  Limits: batch * n_kv_heads <= EA_SELECT_STATIC_MAX_UNITS and
+ * n <= EA_SELECT_STATIC_MAX_N, else EA_ERR_UNSUPPORTED (nothing launched).  Every call on a GPU
+ * shares that GPU's array: calls that overlap in time on one GPU (different streams) race;
+ * calls ordered on one stream, or otherwise serialised, are fine. */
+#define EA_SELECT_STATIC_MAX_UNITS 64
+#define EA_SELECT_STATIC_MAX_N (1 << 20)
+ea_status ea_select_static(const ea_params* p, const float* scores, int64_t n, int64_t n_keep,
+                           int32_t* idx, void* stream);
+
 /* Listing 1 gather: row idx[j] of every head of k and v moves to row j of k_out / v_out
  * (same [B, Hkv, n_cap, d] layout).  k_out == k and v_out == v compacts in place; otherwise
  * the outputs must not overlap the inputs.  idx must be strictly ascending with values < n.

@@ -49,6 +49,8 @@ def load_library():
     lib.ea_score.argtypes = [P, VP, VP, I64, I64, VP, VP, VP, VP, SZ, VP]
     lib.ea_select.restype = ctypes.c_int
     lib.ea_select.argtypes = [P, VP, I64, I64, VP, VP, SZ, VP]
+    lib.ea_select_static.restype = ctypes.c_int
+    lib.ea_select_static.argtypes = [P, VP, I64, I64, VP, VP]
     lib.ea_compact.restype = ctypes.c_int
     lib.ea_compact.argtypes = [P, VP, VP, I64, I64, VP, I64, VP, VP, VP, SZ, VP]
     lib.ea_compress_layer.restype = ctypes.c_int
@@ -125,6 +127,11 @@ def score(p, k, v, n, n_cap, mu, sigma, scores, ws, stream=None):
 def select(p, scores, n, n_keep_, idx, ws, stream=None):
     _check(load_library().ea_select(ctypes.byref(p), _ptr(scores), int(n), int(n_keep_), _ptr(idx),
                                     _ptr(ws), _nbytes(ws), _stream(stream)), "ea_select")
+
+
+def select_static(p, scores, n, n_keep_, idx, stream=None):
+    _check(load_library().ea_select_static(ctypes.byref(p), _ptr(scores), int(n), int(n_keep_),
+                                           _ptr(idx), _stream(stream)), "ea_select_static")
 
 
 def compact(p, k, v, n, n_cap, idx, n_keep_, k_out, v_out, ws, stream=None):

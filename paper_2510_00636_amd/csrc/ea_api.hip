@@ -1,6 +1,9 @@
 // extern "C" entry points of libea: host-side validation, then the launch sequence on the
-// caller's stream.  No allocation, no synchronisation, no state besides a cached CU count.
+// caller's stream.  No allocation, no synchronisation, no state besides a cached CU count and
+// the per-device address of the static scratch array of ea_select_static.
 #include <hip/hip_runtime.h>
+
+#include <mutex>
 
 #include "../../include/ea_profile.h"
 #include "ea_kernels.h"
@@ -92,6 +95,31 @@ static bool partly_overlap(const void* a, const void* b, size_t bytes) {
   return x != y && x < y + bytes && y < x + bytes;
 }
 
+// ---- scratch of ea_select_static: the radix histograms and per-block counts of the selection,
+// for callers that cannot hand over (or allocate) a workspace.  Every GPU the library runs on
+// holds its own copy of the array, at its own address, until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress: the address that kernels, and the
+// clearing launch, get is the one that call returns for the current device.
+constexpr int kStaticMaxUnits = EA_SELECT_STATIC_MAX_UNITS;
+constexpr int64_t kStaticMaxN = EA_SELECT_STATIC_MAX_N;
+constexpr size_t kStaticHistWords = (size_t)kStaticMaxUnits * 3 * kSelBins;
+constexpr size_t kStaticBlkWords = (size_t)kStaticMaxUnits * (kStaticMaxN / kSelBlock) * 2;
+static __device__ __align__(256) uint32_t scratch[kStaticHistWords + kStaticBlkWords];
+
+static uint32_t* static_scratch_for_current_device() {
+  static std::mutex mu;
+  static uint32_t* ptr[64] = {nullptr};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    ptr[dev] = (uint32_t*)p;
+  }
+  return ptr[dev];
+}
+
 }  // namespace ea
 
 using namespace ea;
@@ -144,6 +172,25 @@ ea_status ea_select(const ea_params* p, const float* scores, int64_t n, int64_t 
   uint32_t* hist = (uint32_t*)((char*)ws + L.hist);
   EA_TRY(launch_zero(hist, hist_words(d), st));
   EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, (uint32_t*)((char*)ws + L.blk), false, st));
+  return EA_OK;
+}
+
+ea_status ea_select_static(const ea_params* p, const float* scores, int64_t n, int64_t n_keep,
+                           int32_t* idx, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (n < 1 || n_keep < 0 || n_keep > n) return EA_ERR_INVALID_ARG;
+  if (!aligned16(scores) || (n_keep > 0 && !aligned16(idx))) return EA_ERR_INVALID_ARG;
+  if (n > kStaticMaxN || d.units() > kStaticMaxUnits) return EA_ERR_UNSUPPORTED;
+  if (n_keep == 0) return EA_OK;
+  uint32_t* hist = static_scratch_for_current_device();
+  if (!hist) return EA_ERR_DEVICE;
+  hipStream_t st = (hipStream_t)stream;
+  // the array keeps the previous call's contents: the histograms must start at zero (a fill
+  // kernel, so that the call can be captured in a graph); the block counts are overwritten
+  EA_TRY(launch_zero(hist, hist_words(d), st));
+  EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, hist + kStaticHistWords, false, st));
   return EA_OK;
 }
 

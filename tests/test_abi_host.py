@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(lib):
     hdr = "".join(open(os.path.join(ROOT, "include", f)).read()
                   for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
     names = set(re.findall(r"\b(ea_[a-z_0-9]+)\s*\(", hdr))
-    assert {"ea_workspace_bytes", "ea_query_stats", "ea_score", "ea_select",
+    assert {"ea_workspace_bytes", "ea_query_stats", "ea_score", "ea_select", "ea_select_static",
             "ea_compact", "ea_compress_layer", "ea_n_keep", "ea_status_string",
             "ea_compress_layer_timed", "ea_debug_status"} <= names
     for n in names:
@@ -93,6 +93,11 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     # more rows per head than the launch grids cover
     assert lib.ea_select(byref(p), VP(ok), (1 << 26) + 1, 4, VP(ok), VP(ok), 1 << 40, None) == 1
     assert ea.workspace_bytes(p, (1 << 26) + 1, 64) == 0
+    # the allocation-free selection: limits of its static array, then the usual argument checks
+    assert lib.ea_select_static(byref(ea.make_params(65, 1, 1, 64, ea.EA_F32)), VP(ok), 8, 4, VP(ok), None) == 2
+    assert lib.ea_select_static(byref(p), VP(ok), (1 << 20) + 1, 4, VP(ok), None) == 2
+    assert lib.ea_select_static(byref(p), VP(ok), 8, 9, VP(ok), None) == 1
+    assert lib.ea_select_static(byref(p), VP(ok), 8, 0, None, None) == 0
     # n_keep == 0 is a valid no-op (returns before any launch)
     assert lib.ea_select(byref(p), VP(ok), 8, 0, None, VP(ok), 1 << 30, None) == 0
     assert lib.ea_compact(byref(p), VP(ok), VP(2 * ok), 8, 8, None, 0, VP(ok), VP(2 * ok), VP(ok), 1 << 30, None) == 0
