@@ -31,6 +31,8 @@ struct ScorePlan {
   int nfrag;    // 1 KiB fragments per (unit, pass)
   int span;     // keys per workgroup were the head split evenly (the kernel deals tiles by ticket)
   int nchunk;   // workgroups per unit = ceil(n / span)
+  int hw;       // 1: the register-fragment kernel (one wavefront per query head, d = 128, groups of four)
+  int tpt;      // that kernel: tiles of 32 keys per ticket (1 or 4)
   int pg;       // keys per softmax partial (max, sum exp): partial j covers keys [j*pg, (j+1)*pg)
   int npart;    // partials per query head = ceil(n / pg)
   size_t lds_bytes;

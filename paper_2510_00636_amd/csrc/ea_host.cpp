@@ -39,6 +39,31 @@ ea_status check_params(const ea_params* p, Dims* d) {
 // staging buffers, and the template instance (GH) that covers ceil(G / passes) heads.
 ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
   ScorePlan s;
+  s.hw = 0;
+  s.tpt = 1;
+  if (d.D == 128 && d.dtype == EA_BF16 && d.G % 4 == 0 && n >= 2048) {
+    // groups of four query heads at d = 128: fragments in registers, one wavefront per head,
+    // two workgroups of four wavefronts per CU
+    s.hw = 1;
+    s.GH = 4;
+    s.passes = d.G / 4;
+    s.NW = 4;
+    s.nfrag = 4 * frags_per_head(128) + 2 * ksteps(128);
+    s.lds_bytes = 0;
+    const int64_t ntiles = (n + 31) / 32;
+    int64_t wgs = 2 * (int64_t)num_cu / ((int64_t)d.units() * s.passes);
+    if (wgs < 1) wgs = 1;
+    if (wgs > 1024) wgs = 1024;
+    // a ticket is four tiles where that still leaves every workgroup several tickets
+    s.tpt = (ntiles + 3) / 4 >= 4 * wgs ? 4 : 1;
+    const int64_t nblocks = (ntiles + s.tpt - 1) / s.tpt;
+    if (wgs > nblocks) wgs = nblocks;
+    s.nchunk = (int)wgs;
+    s.span = (int)((n + wgs - 1) / wgs);
+    s.pg = 32 * s.tpt;
+    s.npart = (int)nblocks;
+    return s;
+  }
   const int NF = frags_per_head(d.D), NKS = ksteps(d.D);
   const size_t lds_max = 160 * 1024, slack = 1024;
   const int inst64[] = {1, 2, 4, 8}, inst128[] = {1, 2, 3, 4, 5}, inst256[] = {1};
@@ -88,7 +113,7 @@ WsLayout make_ws_layout(const Dims& d, int64_t n, int64_t window) {
   w.logits = take(qh * (size_t)n * 8);          // fp32 logits (bf16 path) or fp64 (fp32 path)
   w.vnorm = take(un * (size_t)n * sizeof(float));
   // (max, sum exp) partials: float2 per fixed block of keys (bf16 path), double2 per chunk (fp32 path)
-  size_t part_bytes = qh * (size_t)sp.npart * 8;
+  size_t part_bytes = qh * (((size_t)n + 31) / 32) * 8;     // the finest block any plan uses
   if (part_bytes < qh * 1024 * 16) part_bytes = qh * 1024 * 16;
   w.part = take(part_bytes);
   w.lse = take(qh * sizeof(double));

@@ -28,10 +28,12 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
   a.passes = sp.passes;
   a.nchunk = sp.nchunk;
   a.npart = sp.npart;
+  a.tpt = sp.tpt;
   a.units = d.units();
   a.nfrag = sp.nfrag;
   a.tickets = tickets;
   a.ticket_stride = ticket_stride;
+  if (sp.hw) return launch_score_hw(a, sp, st);
   switch (d.D) {
     case 64: return launch_score_mfma_d64(a, sp, st);
     case 128: return sp.GH <= 3 ? launch_score_mfma_d128(a, sp, st) : launch_score_mfma_d128b(a, sp, st);

@@ -32,7 +32,8 @@ struct ScoreArgs {
   float* vnorm;
   float2* part;
   int G, passes, nchunk, units, nfrag;     // nchunk: workgroups per (unit, pass)
-  int npart;              // (max, sum exp) partials per query head: partial j covers keys [32j, 32j+32)
+  int npart;              // (max, sum exp) partials per query head: partial j covers keys [pg*j, pg*j + pg)
+  int tpt;                // register-fragment kernel: tiles per ticket (pg = 32 * tpt); else unused
   uint32_t* tickets;      // tickets + unit * ticket_stride + pass * kTicketWays + way: tile counters, zero at launch
   int ticket_stride;
 };
@@ -482,5 +483,7 @@ hipError_t launch_score_mfma_d64(const ScoreArgs& a, const ScorePlan& sp, hipStr
 hipError_t launch_score_mfma_d128(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
 hipError_t launch_score_mfma_d128b(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
 hipError_t launch_score_mfma_d256(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
+// ea_score_hw.hip: fragments in registers, one wavefront per query head (d = 128, groups of four)
+hipError_t launch_score_hw(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
 
 }  // namespace ea
