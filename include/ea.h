@@ -123,6 +123,37 @@ ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t windo
                             int64_t n_cap, int64_t n_keep, float* scores_out, int32_t* idx_out,
                             void* ws, size_t ws_bytes, void* stream);
 
+/* The cheap scorers of the paper's decoding comparison (Sec. 3.1, "Baselines"), each from the one
+ * sentence the paper gives it, producing scores[B, Hkv, n] for the same ea_select / ea_compact
+ * back half (larger score = kept first):
+ *   EA_SCORER_KNORM      "preserving keys with the lowest L2 norm":  1 / ||k_i||_2
+ *   EA_SCORER_STREAMING  "maintains initial sink tokens": +inf for the first n_sink pairs, i + 1
+ *                        for the others (the rest of the budget goes to the most recent pairs);
+ *                        n <= 2^24 (positions must be exact in fp32), else EA_ERR_UNSUPPORTED
+ *   EA_SCORER_KEYDIFF    "distance metrics between key embeddings":  1 - cos(k_i, a), a = mean of
+ *                        the head's unit-normalised keys (a key of zero norm counts as zero)
+ * Reads k rows < n (twice for KEYDIFF), never v.  n_sink is only used by STREAMING (0 <= n_sink). */
+typedef enum { EA_SCORER_KNORM = 0, EA_SCORER_STREAMING = 1, EA_SCORER_KEYDIFF = 2 } ea_scorer;
+ea_status ea_score_baseline(const ea_params* p, int32_t scorer, const void* k, int64_t n, int64_t n_cap,
+                            int64_t n_sink, float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/* Order-free compaction, in place.  Attention over the cache is a sum over cached pairs (Eq. 2-3)
+ * and every key carries its rotary position (Eq. 1), so the kept pairs need not keep their order:
+ * kept rows below n_keep stay where they are, the kept rows at or beyond n_keep fill, in ascending
+ * order, the evicted positions below n_keep, in ascending order.  Rows >= n_keep are left as they
+ * were.  idx as for ea_compact.  perm_out (nullable, [B, Hkv, n_keep] int32) receives, for every
+ * position of the compacted cache, the row it held before.  Needs no scratch. */
+ea_status ea_compact_unordered(const ea_params* p, void* k, void* v, int64_t n, int64_t n_cap,
+                               const int32_t* idx, int64_t n_keep, int32_t* perm_out, void* stream);
+
+/* ea_compress_layer with the order-free compaction as its last step (the decode-time use: few
+ * pairs are evicted per pass, so few rows move).  idx_out is still the ascending kept list. */
+ea_status ea_compress_layer_unordered(const ea_params* p, const void* q_win, int64_t window,
+                                      int64_t q_pos0, const double* inv_freq, int64_t t_next, void* k,
+                                      void* v, int64_t n, int64_t n_cap, int64_t n_keep,
+                                      float* scores_out, int32_t* idx_out, int32_t* perm_out, void* ws,
+                                      size_t ws_bytes, void* stream);
+
 /* Listing 1: int(n * (1 - ratio)) in IEEE double, truncated toward zero; -1 if ratio is
  * outside [0, 1] or n < 0.  Host only. */
 int64_t ea_n_keep(int64_t n, double ratio);

@@ -55,6 +55,12 @@ def load_library():
     lib.ea_compact.argtypes = [P, VP, VP, I64, I64, VP, I64, VP, VP, VP, SZ, VP]
     lib.ea_compress_layer.restype = ctypes.c_int
     lib.ea_compress_layer.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, VP, VP, SZ, VP]
+    lib.ea_score_baseline.restype = ctypes.c_int
+    lib.ea_score_baseline.argtypes = [P, ctypes.c_int32, VP, I64, I64, I64, VP, VP, SZ, VP]
+    lib.ea_compact_unordered.restype = ctypes.c_int
+    lib.ea_compact_unordered.argtypes = [P, VP, VP, I64, I64, VP, I64, VP, VP]
+    lib.ea_compress_layer_unordered.restype = ctypes.c_int
+    lib.ea_compress_layer_unordered.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, VP, VP, VP, SZ, VP]
     lib.ea_compress_layer_timed.restype = ctypes.c_int
     lib.ea_compress_layer_timed.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, SZ, VP,
                                             ctypes.POINTER(ctypes.c_float)]
@@ -147,6 +153,31 @@ def compress_layer(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n
                                             int(n_cap), int(n_keep_), _ptr(scores_out),
                                             _ptr(idx_out), _ptr(ws), _nbytes(ws), _stream(stream)),
            "ea_compress_layer")
+
+
+SCORER_KNORM, SCORER_STREAMING, SCORER_KEYDIFF = 0, 1, 2
+
+
+def score_baseline(p, scorer, k, n, n_cap, n_sink, scores, ws, stream=None):
+    _check(load_library().ea_score_baseline(ctypes.byref(p), int(scorer), _ptr(k), int(n), int(n_cap),
+                                            int(n_sink), _ptr(scores), _ptr(ws), _nbytes(ws),
+                                            _stream(stream)), "ea_score_baseline")
+
+
+def compact_unordered(p, k, v, n, n_cap, idx, n_keep_, perm_out=None, stream=None):
+    _check(load_library().ea_compact_unordered(ctypes.byref(p), _ptr(k), _ptr(v), int(n), int(n_cap),
+                                               _ptr(idx), int(n_keep_), _ptr(perm_out), _stream(stream)),
+           "ea_compact_unordered")
+
+
+def compress_layer_unordered(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep_,
+                             scores_out, idx_out, perm_out, ws, stream=None):
+    _check(load_library().ea_compress_layer_unordered(ctypes.byref(p), _ptr(q_win), int(window),
+                                                      int(q_pos0), _ptr(inv_freq), int(t_next), _ptr(k),
+                                                      _ptr(v), int(n), int(n_cap), int(n_keep_),
+                                                      _ptr(scores_out), _ptr(idx_out), _ptr(perm_out),
+                                                      _ptr(ws), _nbytes(ws), _stream(stream)),
+           "ea_compress_layer_unordered")
 
 
 N_STAGES = 6

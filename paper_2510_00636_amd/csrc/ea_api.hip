@@ -226,18 +226,20 @@ ea_status ea_compact(const ea_params* p, const void* k, const void* v, int64_t n
   return EA_OK;
 }
 
+// unordered: the order-free compaction (perm_out then receives the source row of every position)
 static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t window,
                                int64_t q_pos0, const double* inv_freq, int64_t t_next, void* k,
                                void* v, int64_t n, int64_t n_cap, int64_t n_keep, float* scores_out,
                                int32_t* idx_out, void* ws, size_t ws_bytes, void* stream,
-                               hipEvent_t* ev) {
+                               hipEvent_t* ev, bool unordered = false, int32_t* perm_out = nullptr) {
   Dims d;
   ea_status s = check_params(p, &d);
   if (s != EA_OK) return s;
   if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || k == v || !inv_freq ||
       ((uintptr_t)inv_freq & 7u))
     return EA_ERR_INVALID_ARG;
-  if ((scores_out && !aligned16(scores_out)) || (idx_out && !aligned16(idx_out)))
+  if ((scores_out && !aligned16(scores_out)) || (idx_out && !aligned16(idx_out)) ||
+      (perm_out && !aligned16(perm_out)))
     return EA_ERR_INVALID_ARG;
   if (window < 1 + d.ddof || q_pos0 < 0 || t_next < 0) return EA_ERR_INVALID_ARG;
   if (window > kMaxWindow) return EA_ERR_UNSUPPORTED;
@@ -269,7 +271,9 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
   if (n_keep > 0)
     EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, (uint32_t*)(w + L.blk), true, st));
   if (ev) EA_TRY(hipEventRecord(ev[5], st));
-  if (n_keep > 0)
+  if (n_keep > 0 && unordered)
+    EA_TRY(launch_compact_fill(d, k, v, n, n_cap, idx, n_keep, perm_out, st));
+  else if (n_keep > 0)
     EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k, v, flags, hist + 2 * kSelBins + kStatusSlot, st));
   if (ev) EA_TRY(hipEventRecord(ev[6], st));
   return EA_OK;
@@ -281,6 +285,46 @@ ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t windo
                             void* ws, size_t ws_bytes, void* stream) {
   return compress_impl(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep,
                        scores_out, idx_out, ws, ws_bytes, stream, nullptr);
+}
+
+ea_status ea_score_baseline(const ea_params* p, int32_t scorer, const void* k, int64_t n, int64_t n_cap,
+                            int64_t n_sink, float* scores, void* ws, size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (scorer != EA_SCORER_KNORM && scorer != EA_SCORER_STREAMING && scorer != EA_SCORER_KEYDIFF)
+    return EA_ERR_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(scores)) return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > kMaxN || n_sink < 0) return EA_ERR_INVALID_ARG;
+  if (scorer == EA_SCORER_STREAMING && n > ((int64_t)1 << 24)) return EA_ERR_UNSUPPORTED;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  EA_TRY(launch_baseline(d, scorer, k, n, n_cap, n_sink, scores, (float*)((char*)ws + L.base),
+                         (hipStream_t)stream));
+  return EA_OK;
+}
+
+ea_status ea_compact_unordered(const ea_params* p, void* k, void* v, int64_t n, int64_t n_cap,
+                               const int32_t* idx, int64_t n_keep, int32_t* perm_out, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(k) || !aligned16(v) || k == v) return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > kMaxN || n_keep < 0 || n_keep > n) return EA_ERR_INVALID_ARG;
+  if (partly_overlap(k, v, (size_t)d.units() * (size_t)n_cap * d.D * d.esize())) return EA_ERR_INVALID_ARG;
+  if (n_keep > 0 && (!aligned16(idx) || (perm_out && !aligned16(perm_out)))) return EA_ERR_INVALID_ARG;
+  if (n_keep == 0) return EA_OK;
+  EA_TRY(launch_compact_fill(d, k, v, n, n_cap, idx, n_keep, perm_out, (hipStream_t)stream));
+  return EA_OK;
+}
+
+ea_status ea_compress_layer_unordered(const ea_params* p, const void* q_win, int64_t window,
+                                      int64_t q_pos0, const double* inv_freq, int64_t t_next, void* k,
+                                      void* v, int64_t n, int64_t n_cap, int64_t n_keep,
+                                      float* scores_out, int32_t* idx_out, int32_t* perm_out, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  return compress_impl(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep,
+                       scores_out, idx_out, ws, ws_bytes, stream, nullptr, true, perm_out);
 }
 
 ea_status ea_compress_layer_timed(const ea_params* p, const void* q_win, int64_t window,

@@ -39,7 +39,7 @@ struct ScorePlan {
 };
 
 struct WsLayout {
-  size_t tab, mu, sigma, frags, post, logits, vnorm, part, lse, scores, idx, hist, blk, flags, total;
+  size_t tab, mu, sigma, frags, post, logits, vnorm, part, lse, scores, idx, base, hist, blk, flags, total;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -57,6 +57,7 @@ constexpr int kTicketSlot = 1040;
 constexpr uint32_t kStatusBadScore = 1u;      // ea_select met a negative or NaN score
 constexpr uint32_t kStatusCompactWait = 2u;   // in-place ea_compact gave up waiting: stores skipped
 constexpr uint32_t kStatusBadIndex = 4u;      // ea_compact met an idx list that is not strictly ascending in [j, n)
+constexpr int kBaselineChunks = 256;          // most row chunks per head in the KeyDiff mean
 constexpr int kCompactTicketStride = 64;      // words per (unit, tensor) at the head of the flag region
 
 // fragments per head of the triangular Sigma tiling, and per pass

@@ -178,6 +178,98 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Order-free compaction.  Attention over the cache is a sum over cached pairs (Eq. 2-3 of the
+// paper) and the keys carry their rotary position inside them (Eq. 1), so the order of the kept
+// pairs is free.  Then only the kept rows at or beyond the new length have to move: row idx[j0 + i]
+// (j0 = number of kept rows below n_keep) goes to the i-th evicted position below n_keep.  The
+// i-th such hole sits right after j kept rows, j being the smallest index with idx[j] - j > i
+// (idx[j] - j = holes before kept row j), i.e. at position i + j.  Sources lie at or beyond
+// n_keep and destinations below it, on rows nobody reads: no ordering between workgroups.
+constexpr int kFillRows = 64;       // moved rows per workgroup
+
+struct FillArgs {
+  u32x4* t[2];
+  const int32_t* idx;
+  int32_t* perm;      // nullable: [units][n_keep], source row now at each position
+  long long n_cap;
+  int n, n_keep, units, nch;
+};
+
+template <int RB>
+__global__ __launch_bounds__(256) void k_compact_fill(FillArgs a) {
+  constexpr int CPR = RB / 16;
+  constexpr int NLD = kFillRows * CPR / 256;
+  __shared__ int s_j0;
+  __shared__ int s_src[kFillRows], s_dst[kFillRows];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int ntu = 2 * a.units;
+  const int tu = blockIdx.x % ntu, c = blockIdx.x / ntu;
+  const int unit = tu >> 1, tensor = tu & 1;
+  const int32_t* idx = a.idx + (size_t)unit * a.n_keep;
+  if (tid < 64) {
+    const int j0 = first_true(a.n_keep, lane, [&](int x) { return idx[x] >= a.n_keep; });
+    if (lane == 0) s_j0 = j0;
+  }
+  __syncthreads();
+  const int j0 = s_j0, m = a.n_keep - j0;
+  int32_t* perm = a.perm ? a.perm + (size_t)unit * a.n_keep : nullptr;
+  if (perm && tensor == 0)          // rows that stay: every workgroup of the unit takes a stride of them
+    for (int j = c * 256 + tid; j < j0; j += a.nch * 256) perm[idx[j]] = idx[j];
+  const int i0 = c * kFillRows;
+  if (i0 >= m) return;
+  if (tid < kFillRows) {
+    const int i = min(i0 + tid, m - 1);
+    int lo = 0, hi = j0;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (idx[mid] - mid > i) hi = mid; else lo = mid + 1;
+    }
+    const int src = min(max(idx[j0 + i], 0), a.n - 1), dst = i + lo;   // never outside the tensor
+    s_src[tid] = src;
+    s_dst[tid] = dst;
+    if (perm && tensor == 0 && i0 + tid < m) perm[dst] = src;
+  }
+  __syncthreads();
+  u32x4* base = a.t[tensor] + (size_t)unit * a.n_cap * CPR;
+  u32x4 buf[NLD];
+#pragma unroll
+  for (int q = 0; q < NLD; ++q) {
+    const int e = tid + 256 * q;
+    buf[q] = __builtin_nontemporal_load(&base[(size_t)s_src[e / CPR] * CPR + e % CPR]);
+  }
+#pragma unroll
+  for (int q = 0; q < NLD; ++q) {
+    const int e = tid + 256 * q, row = e / CPR;
+    if (i0 + row < m) __builtin_nontemporal_store(buf[q], &base[(size_t)s_dst[row] * CPR + e % CPR]);
+  }
+}
+
+hipError_t launch_compact_fill(const Dims& d, void* k, void* v, int64_t n, int64_t n_cap,
+                               const int32_t* idx, int64_t n_keep, int32_t* perm, hipStream_t st) {
+  FillArgs a;
+  a.t[0] = (u32x4*)k;
+  a.t[1] = (u32x4*)v;
+  a.idx = idx;
+  a.perm = perm;
+  a.n_cap = n_cap;
+  a.n = (int)n;
+  a.n_keep = (int)n_keep;
+  a.units = d.units();
+  const int64_t most = n_keep < n - n_keep ? n_keep : n - n_keep;      // rows that can have to move
+  a.nch = (int)((most + kFillRows - 1) / kFillRows);
+  if (a.nch < 1) a.nch = 1;
+  const unsigned grid = 2u * a.units * a.nch;
+  switch (d.D * d.esize()) {
+    case 128: k_compact_fill<128><<<grid, 256, 0, st>>>(a); break;
+    case 256: k_compact_fill<256><<<grid, 256, 0, st>>>(a); break;
+    case 512: k_compact_fill<512><<<grid, 256, 0, st>>>(a); break;
+    case 1024: k_compact_fill<1024><<<grid, 256, 0, st>>>(a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                           const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
                           uint32_t* flags, uint32_t* status, hipStream_t st) {

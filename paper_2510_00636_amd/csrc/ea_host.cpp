@@ -119,6 +119,7 @@ WsLayout make_ws_layout(const Dims& d, int64_t n, int64_t window) {
   w.lse = take(qh * sizeof(double));
   w.scores = take(un * (size_t)n * sizeof(float));
   w.idx = take(un * (size_t)n * sizeof(int32_t));
+  w.base = take(un * kBaselineChunks * d.D * sizeof(float));    // KeyDiff partial sums
   w.hist = take(un * 3 * kSelBins * sizeof(uint32_t) + 256);
   size_t nblk = ((size_t)n + kSelBlock - 1) / kSelBlock;
   w.blk = take(un * nblk * 2 * sizeof(uint32_t));

@@ -44,6 +44,15 @@ hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n
                           const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
                           uint32_t* flags, uint32_t* status, hipStream_t st);
 
+// order-free variant, in place: only the kept rows at or beyond n_keep move, into the evicted
+// positions below it; perm (nullable) [units][n_keep] receives the source row of every position
+hipError_t launch_compact_fill(const Dims& d, void* k, void* v, int64_t n, int64_t n_cap,
+                               const int32_t* idx, int64_t n_keep, int32_t* perm, hipStream_t st);
+
+// ea_baselines.hip: scorer = ea_scorer; scratch: units * kBaselineChunks * D floats
+hipError_t launch_baseline(const Dims& d, int kind, const void* k, int64_t n, int64_t n_cap,
+                           int64_t n_sink, float* scores, float* scratch, hipStream_t st);
+
 int device_num_cu();
 
 // hipFuncSetAttribute(MaxDynamicSharedMemorySize) once per (kernel, device) instead of on every

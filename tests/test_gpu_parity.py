@@ -456,3 +456,107 @@ def test_status_word_reports_bad_scores_and_bad_indices():
         ko, vo = (kd, vd) if inplace else (torch.zeros_like(kd), torch.zeros_like(vd))
         ea.compact(p, kd, vd, n, n, P.to_dev(np.broadcast_to(twisted, (1, 2, n_keep)).copy()), n_keep, ko, vo, ws)
         assert ea.debug_status(p, n, 1, ws) & ea.STATUS_BAD_INDEX
+
+
+# ------------------------------------------------------------------- order-free compaction
+@pytest.mark.parametrize("shape", ["d128bf16", "d256bf16", "d64f32"])
+def test_compact_unordered_bit_exact(shape):
+    """Rows in front are exactly the oracle's permutation of the kept rows (so also the same set),
+    rows from n_keep on are untouched, and perm_out names the source of every position."""
+    import torch
+    from oracle import ea_extensions as X
+    cfg = {"d128bf16": CONFIGS["c2"].with_(n_kv_heads=2, n_q_heads=2),
+           "d256bf16": CONFIGS["c4"].with_(batch=1, n_kv_heads=2, n_q_heads=2),
+           "d64f32": CONFIGS["c1"]}[shape]
+    p = P.params_for(cfg)
+    n, n_cap = 3001, 3050
+    r = np.random.default_rng(21)
+    B, H, d = cfg.batch, cfg.n_kv_heads, cfg.head_dim
+    if cfg.dtype == "bf16":
+        k = r.integers(0, 2 ** 16, (B, H, n_cap, d)).astype(np.uint16)
+        v = r.integers(0, 2 ** 16, (B, H, n_cap, d)).astype(np.uint16)
+    else:
+        k = r.standard_normal((B, H, n_cap, d)).astype(np.float32)
+        v = r.standard_normal((B, H, n_cap, d)).astype(np.float32)
+    for name, m in _masks(n, r):
+        idx = np.broadcast_to(m, (B, H, len(m))).copy()
+        if name == "half_random":
+            for b in range(B):
+                for h in range(H):
+                    idx[b, h] = np.sort(r.choice(n, len(m), replace=False))
+        nk = len(m)
+        kd, vd = P.to_dev(k), P.to_dev(v)
+        perm = torch.full((B, H, nk), -1, dtype=torch.int32, device="cuda")
+        ea.compact_unordered(p, kd, vd, n, n_cap, P.to_dev(idx.astype(np.int32)), nk, perm)
+        torch.cuda.synchronize()
+        ko, vo = P.to_host(kd), P.to_host(vd)
+        rk, rv, rperm = X.compact_unordered(k, v, idx.astype(np.int64))
+        assert np.array_equal(perm.cpu().numpy(), rperm), name
+        assert np.array_equal(ko[:, :, :nk], rk) and np.array_equal(vo[:, :, :nk], rv), name
+        assert np.array_equal(ko[:, :, nk:], k[:, :, nk:]) and np.array_equal(vo[:, :, nk:], v[:, :, nk:]), name
+
+
+def test_compress_layer_unordered_decode_shape():
+    """The decode-time pass (4608 -> 4096 pairs) with the order-free last step: same scores and kept
+    set as the ordered call, rows in front = the oracle's permutation."""
+    import torch
+    from oracle import ea_extensions as X
+    cfg = CONFIGS["c5"]
+    lay = make_layer(cfg, n=4608, window=512, pos0=20000)
+    n, w, n_keep = 4608, 512, 4096
+    ref = P.run_compress_layer(cfg, lay, n_keep)
+    p = P.params_for(cfg)
+    ws = P.workspace(p, n, w)
+    kd, vd = P.to_dev(lay["k"]), P.to_dev(lay["v"])
+    sc = torch.empty(cfg.batch, cfg.n_kv_heads, n, dtype=torch.float32, device="cuda")
+    idx = torch.empty(cfg.batch, cfg.n_kv_heads, n_keep, dtype=torch.int32, device="cuda")
+    perm = torch.empty_like(idx)
+    ea.compress_layer_unordered(p, P.to_dev(lay["q_win"]), w, lay["q_pos0"], P.to_dev(lay["inv_freq"]),
+                                lay["t_next"], kd, vd, n, n, n_keep, sc, idx, perm, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(sc.cpu().numpy(), ref["scores"]) and np.array_equal(idx.cpu().numpy(), ref["idx"])
+    rk, rv, rperm = X.compact_unordered(lay["k"], lay["v"], ref["idx"].astype(np.int64))
+    assert np.array_equal(perm.cpu().numpy(), rperm)
+    assert np.array_equal(P.to_host(kd)[:, :, :n_keep], rk) and np.array_equal(P.to_host(vd)[:, :, :n_keep], rv)
+
+
+# ------------------------------------------------------------------- comparison scorers
+@pytest.mark.parametrize("name", ["c1", "c2mini", "c4mini", "d64bf16"])
+def test_baseline_scorers(name):
+    """KNorm, StreamingLLM and KeyDiff scores against their oracle definitions, and the kept sets
+    they lead to through ea_select."""
+    import torch
+    from oracle import ea_extensions as X
+    cfg, kw = MINI[name]
+    lay = make_layer(cfg, **kw)
+    n = lay["n"]
+    p = P.params_for(cfg)
+    ws = P.workspace(p, n, 1)
+    kd = P.to_dev(lay["k"])
+    k64 = widen(lay["k"])
+    sc = torch.empty(cfg.batch, cfg.n_kv_heads, n, dtype=torch.float32, device="cuda")
+    n_keep = n // 3
+    idx = torch.empty(cfg.batch, cfg.n_kv_heads, n_keep, dtype=torch.int32, device="cuda")
+    for scorer, ref, tol, atol in ((ea.SCORER_KNORM, X.knorm_scores(k64), 1e-5, 0.0),
+                                   (ea.SCORER_STREAMING, X.streaming_scores(cfg.batch, cfg.n_kv_heads, n, 4), 0.0, 0.0),
+                                   (ea.SCORER_KEYDIFF, X.keydiff_scores(k64), 1e-5, 2e-6)):
+        ea.score_baseline(p, scorer, kd, n, n, 4, sc, ws)
+        ea.select(p, sc, n, n_keep, idx, ws)
+        torch.cuda.synchronize()
+        got = sc.cpu().numpy().astype(np.float64)
+        if scorer != ea.SCORER_STREAMING:
+            assert np.all(np.abs(got - ref) <= tol * np.abs(ref) + atol)
+        if scorer == ea.SCORER_STREAMING:
+            assert np.array_equal(got, ref)
+            assert np.array_equal(idx.cpu().numpy().astype(np.int64), O.select(ref, n_keep))
+        else:
+            P.check_idx_exact_given_scores(idx.cpu().numpy(), sc.cpu().numpy(), n_keep)
+            # kept set vs the oracle's, up to scores within the tolerance band of the threshold
+            for b in range(cfg.batch):
+                for h in range(cfg.n_kv_heads):
+                    s = ref[b, h]
+                    thr = np.sort(s)[n - n_keep]
+                    band = tol * abs(thr) + atol
+                    kept = np.zeros(n, bool)
+                    kept[idx[b, h].cpu().numpy()] = True
+                    assert kept[s > thr + 2 * band].all() and not kept[s < thr - 2 * band].any()
