@@ -123,6 +123,26 @@ ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t windo
                             int64_t n_cap, int64_t n_keep, float* scores_out, int32_t* idx_out,
                             void* ws, size_t ws_bytes, void* stream);
 
+/* Sec. 2.2, "Head-Adaptive Compression": one budget of Hkv * n_keep pairs per (sequence, layer),
+ * shared by the layer's KV heads, "allowing more important heads to retain more KV pairs".  The
+ * paper only cites the idea; the rule here: every head first keeps its own `floor` best pairs
+ * (0 <= floor <= n_keep), the rest of the budget goes to the best remaining pairs of the whole
+ * layer; equal scores go to the lower head, then to the lower position.
+ *   idx      [B, Hkv, n] int32 (a head's list starts at multiples of n): the first lengths[b,h]
+ *            entries of each list are that head's kept positions, ascending; the rest is untouched
+ *   lengths  [B, Hkv] int32 DEVICE; their sum over a sequence's heads is Hkv * n_keep
+ * Scores as for ea_select.  Needs Hkv * n <= 2^26. */
+ea_status ea_select_adaptive(const ea_params* p, const float* scores, int64_t n, int64_t n_keep,
+                             int64_t floor, int32_t* idx, int32_t* lengths, void* ws, size_t ws_bytes,
+                             void* stream);
+
+/* Listing 1's gather with a kept count per head, in place: row idx[b,h,j] of head (b,h) moves to
+ * row j for j < lengths[b,h] (idx, lengths as written by ea_select_adaptive).  Rows from
+ * lengths[b,h] on are left as they were. */
+ea_status ea_compact_ragged(const ea_params* p, void* k, void* v, int64_t n, int64_t n_cap,
+                            const int32_t* idx, const int32_t* lengths, void* ws, size_t ws_bytes,
+                            void* stream);
+
 /* The cheap scorers of the paper's decoding comparison (Sec. 3.1, "Baselines"), each from the one
  * sentence the paper gives it, producing scores[B, Hkv, n] for the same ea_select / ea_compact
  * back half (larger score = kept first):

@@ -287,6 +287,64 @@ ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t windo
                        scores_out, idx_out, ws, ws_bytes, stream, nullptr);
 }
 
+ea_status ea_select_adaptive(const ea_params* p, const float* scores, int64_t n, int64_t n_keep,
+                             int64_t floor, int32_t* idx, int32_t* lengths, void* ws, size_t ws_bytes,
+                             void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (n < 1 || n > kMaxN || n_keep < 0 || n_keep > n || floor < 0 || floor > n_keep) return EA_ERR_INVALID_ARG;
+  if (!aligned16(scores) || !aligned16(idx) || !lengths || ((uintptr_t)lengths & 3u)) return EA_ERR_INVALID_ARG;
+  if ((int64_t)d.Hkv * n > kMaxN) return EA_ERR_UNSUPPORTED;      // the pooled list of a layer
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  char* w = (char*)ws;
+  uint32_t* hist = (uint32_t*)(w + L.hist);
+  uint32_t* blk = (uint32_t*)(w + L.blk);
+  int32_t* flat = (int32_t*)(w + L.idx);                // [B][Hkv * n_keep], ascending in [0, Hkv * n)
+  const float* pooled = scores;
+  if (floor > 0 && n_keep > 0) {
+    // every head's own best `floor` pairs, then a copy of the scores with those lifted to +inf
+    int32_t* top = (int32_t*)(w + L.logits);            // [units][floor]
+    float* lifted = (float*)(w + L.scores);
+    EA_TRY(launch_zero(hist, hist_words(d), st));
+    EA_TRY(launch_select(d, scores, n, floor, top, hist, blk, false, st));
+    EA_TRY(hipMemcpyAsync(lifted, scores, (size_t)d.units() * n * sizeof(float), hipMemcpyDeviceToDevice, st));
+    EA_TRY(launch_mark_inf(lifted, top, d.units(), n, floor, st));
+    pooled = lifted;
+  }
+  Dims layer = d;                                       // one pooled list per sequence
+  layer.Hq = d.G;
+  layer.Hkv = 1;
+  if (n_keep > 0) {
+    EA_TRY(launch_zero(hist, hist_words(d), st));
+    EA_TRY(launch_select(layer, pooled, (int64_t)d.Hkv * n, (int64_t)d.Hkv * n_keep, flat, hist, blk, false, st));
+  }
+  EA_TRY(launch_split_pooled(flat, d.B, d.Hkv, n, n_keep, idx, lengths, st));
+  return EA_OK;
+}
+
+ea_status ea_compact_ragged(const ea_params* p, void* k, void* v, int64_t n, int64_t n_cap,
+                            const int32_t* idx, const int32_t* lengths, void* ws, size_t ws_bytes,
+                            void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(k) || !aligned16(v) || k == v || !aligned16(idx) || !lengths || ((uintptr_t)lengths & 3u))
+    return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > kMaxN) return EA_ERR_INVALID_ARG;
+  if (partly_overlap(k, v, (size_t)d.units() * (size_t)n_cap * d.D * d.esize())) return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  uint32_t* flags = (uint32_t*)((char*)ws + L.flags);
+  uint32_t* status = (uint32_t*)((char*)ws + L.hist) + 2 * kSelBins + kStatusSlot;
+  EA_TRY(launch_zero(flags, flag_words(d, n), st, status));
+  EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n, k, v, flags, status, st, lengths, n));
+  return EA_OK;
+}
+
 ea_status ea_score_baseline(const ea_params* p, int32_t scorer, const void* k, int64_t n, int64_t n_cap,
                             int64_t n_sink, float* scores, void* ws, size_t ws_bytes, void* stream) {
   Dims d;

@@ -32,6 +32,8 @@ struct CompactArgs {
   uint32_t* flags;    // [2*units][kTicketStride] ticket counters, then [2*units][nch] loaded flags
   int inplace;
   uint32_t* status;   // status word (bits kStatusCompactWait, kStatusBadIndex)
+  const int32_t* lengths;   // nullable: kept rows of every unit (head-adaptive budgets); then n_keep is
+  long long idx_stride;     // only the grid's upper bound, and a unit's list starts at unit * idx_stride
 };
 
 // First x in [0, c) for which the monotone predicate pred(x) (false ... false true ... true)
@@ -86,8 +88,10 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   __syncthreads();
   const int c = s_c;
   const int unit = tu >> 1, tensor = tu & 1;
-  const int j0 = c * kCompactRows, j1 = min(j0 + kCompactRows, a.n_keep);
-  const int32_t* idx = a.idx + (size_t)unit * a.n_keep;
+  const int n_keep = a.lengths ? a.lengths[unit] : a.n_keep;
+  const int j0 = c * kCompactRows, j1 = min(j0 + kCompactRows, n_keep);
+  if (j0 >= n_keep) return;           // ragged lists: this unit has fewer chunks than the grid allows for
+  const int32_t* idx = a.idx + (size_t)unit * a.idx_stride;
   const u32x4* src = a.src[tensor] + (size_t)unit * a.n_cap * CPR;
   u32x4* dst = a.dst[tensor] + (size_t)unit * a.n_cap * CPR;
   // Rows are strictly ascending with idx[j] >= j, so idx[j1-1] == j1-1 means nothing moves.  Only
@@ -272,8 +276,11 @@ hipError_t launch_compact_fill(const Dims& d, void* k, void* v, int64_t n, int64
 
 hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                           const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
-                          uint32_t* flags, uint32_t* status, hipStream_t st) {
+                          uint32_t* flags, uint32_t* status, hipStream_t st, const int32_t* lengths,
+                          int64_t idx_stride) {
   CompactArgs a;
+  a.lengths = lengths;
+  a.idx_stride = lengths ? idx_stride : n_keep;
   a.n = (int)n;
   a.src[0] = (const u32x4*)k;
   a.src[1] = (const u32x4*)v;

@@ -42,7 +42,15 @@ hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st, uint32_t* extr
 // ea_compact.hip
 hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                           const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
-                          uint32_t* flags, uint32_t* status, hipStream_t st);
+                          uint32_t* flags, uint32_t* status, hipStream_t st,
+                          const int32_t* lengths = nullptr, int64_t idx_stride = 0);
+// lengths != nullptr: unit u keeps lengths[u] <= n_keep rows, listed from idx + u * idx_stride
+
+// ea_select.hip, head-adaptive budgets: +inf into scores[unit][idx[unit][j]], j < n_mark; then the
+// split of a pooled, ascending list flat[b][0 .. H*n_keep) over [H][n] into per-head lists
+hipError_t launch_mark_inf(float* scores, const int32_t* idx, int units, int64_t n, int64_t n_mark, hipStream_t st);
+hipError_t launch_split_pooled(const int32_t* flat, int B, int H, int64_t n, int64_t n_keep, int32_t* idx,
+                               int32_t* lengths, hipStream_t st);
 
 // order-free variant, in place: only the kept rows at or beyond n_keep move, into the evicted
 // positions below it; perm (nullable) [units][n_keep] receives the source row of every position

@@ -400,4 +400,50 @@ hipError_t launch_select(const Dims& d, const float* scores, int64_t n, int64_t 
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Head-adaptive budgets (Sec. 2.2, "Head-Adaptive Compression"): the selection runs once over the
+// pooled scores of a layer's KV heads, [H][n] read as one list of H*n, after every head's own
+// `floor` best pairs have been lifted to +inf so that the pooled selection takes them first.
+__global__ void k_mark_inf(float* __restrict__ scores, const int32_t* __restrict__ idx, long long n,
+                           long long n_mark) {
+  const long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int unit = blockIdx.y;
+  if (j < n_mark) scores[(size_t)unit * n + idx[(size_t)unit * n_mark + j]] = INFINITY;
+}
+
+hipError_t launch_mark_inf(float* scores, const int32_t* idx, int units, int64_t n, int64_t n_mark, hipStream_t st) {
+  if (n_mark == 0) return hipSuccess;
+  dim3 grid((unsigned)((n_mark + 255) / 256), units);
+  k_mark_inf<<<grid, 256, 0, st>>>(scores, idx, n, n_mark);
+  return hipGetLastError();
+}
+
+// One workgroup per (sequence, head): the head's stretch of the pooled ascending list is found by
+// two binary searches, then copied with the head's offset taken off.
+__global__ __launch_bounds__(256) void k_split_pooled(const int32_t* __restrict__ flat, int H, long long n,
+                                                      long long n_keep, int32_t* __restrict__ idx,
+                                                      int32_t* __restrict__ lengths) {
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  const long long total = (long long)H * n_keep;
+  const int32_t* f = flat + (size_t)b * total;
+  auto lower = [&](long long key) {
+    long long lo = 0, hi = total;
+    while (lo < hi) {
+      const long long mid = (lo + hi) >> 1;
+      if (f[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+  };
+  const long long lo = lower((long long)h * n), hi = lower((long long)(h + 1) * n);
+  if (threadIdx.x == 0) lengths[blockIdx.x] = (int32_t)(hi - lo);
+  int32_t* out = idx + (size_t)blockIdx.x * n;
+  for (long long j = lo + threadIdx.x; j < hi; j += 256) out[j - lo] = f[j] - (int32_t)(h * n);
+}
+
+hipError_t launch_split_pooled(const int32_t* flat, int B, int H, int64_t n, int64_t n_keep, int32_t* idx,
+                               int32_t* lengths, hipStream_t st) {
+  k_split_pooled<<<B * H, 256, 0, st>>>(flat, H, n, n_keep, idx, lengths);
+  return hipGetLastError();
+}
+
 }  // namespace ea

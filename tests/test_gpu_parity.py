@@ -560,3 +560,45 @@ def test_baseline_scorers(name):
                     kept = np.zeros(n, bool)
                     kept[idx[b, h].cpu().numpy()] = True
                     assert kept[s > thr + 2 * band].all() and not kept[s < thr - 2 * band].any()
+
+
+# ------------------------------------------------------------------- head-adaptive budgets
+@pytest.mark.parametrize("n,n_keep,floor", [(700, 300, 0), (700, 300, 40), (700, 300, 300), (700, 0, 0),
+                                            (20000, 9000, 0), (20000, 9000, 500), (5, 3, 1)])
+def test_select_adaptive_and_ragged_compaction(n, n_keep, floor):
+    """Pooled selection over the KV heads of every sequence against the oracle's flat stable sort
+    (bit-exact lists and lengths), then the ragged in-place gather against fancy indexing."""
+    import torch
+    from oracle import ea_extensions as X
+    cfg = CONFIGS["c2"].with_(batch=2, n_kv_heads=4, n_q_heads=4)
+    p = P.params_for(cfg)
+    r = np.random.default_rng(n + n_keep + floor)
+    sc = np.exp(1.5 * r.standard_normal((2, 4, n))).astype(np.float32)
+    sc[:, 1] *= 8.0                                        # a head that earns more than its share
+    sc[0, 2, ::4] = sc[0, 2, 0]                            # ties inside a head
+    sc[1, 0] = sc[1, 3]                                    # ties across heads
+    ws = P.workspace(p, n, 1)
+    idx = torch.full((2, 4, n), -7, dtype=torch.int32, device="cuda")
+    lengths = torch.full((2, 4), -1, dtype=torch.int32, device="cuda")
+    ea.select_adaptive(p, P.to_dev(sc), n, n_keep, floor, idx, lengths, ws)
+    torch.cuda.synchronize()
+    rl, rk = X.select_adaptive(sc.astype(np.float64), n_keep, floor)
+    gl, gi = lengths.cpu().numpy(), idx.cpu().numpy()
+    assert np.array_equal(gl, rl)
+    for b in range(2):
+        for h in range(4):
+            assert np.array_equal(gi[b, h, :gl[b, h]], rk[b][h]), (b, h)
+            assert np.all(gi[b, h, gl[b, h]:] == -7)
+    k = r.integers(0, 2 ** 16, (2, 4, n + 9, 128)).astype(np.uint16)
+    v = r.integers(0, 2 ** 16, (2, 4, n + 9, 128)).astype(np.uint16)
+    kd, vd = P.to_dev(k), P.to_dev(v)
+    ea.compact_ragged(p, kd, vd, n, n + 9, idx, lengths, ws)
+    torch.cuda.synchronize()
+    assert ea.debug_status(p, n, 1, ws) == 0
+    ko, vo = P.to_host(kd), P.to_host(vd)
+    ref = X.compact_ragged(k, v, rk)
+    for b in range(2):
+        for h in range(4):
+            m = gl[b, h]
+            assert np.array_equal(ko[b, h, :m], ref[b][h][0]) and np.array_equal(vo[b, h, :m], ref[b][h][1])
+            assert np.array_equal(ko[b, h, m:], k[b, h, m:]) and np.array_equal(vo[b, h, m:], v[b, h, m:])
