@@ -78,6 +78,16 @@ ea_status ea_query_stats(const ea_params* p, const void* q_win, int64_t window, 
                          const double* inv_freq, int64_t t_next, float* mu, float* sigma,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* Eq. 5-6 as printed, from a buffer of hidden states (Sec. 3.1: "a small buffer of hidden states
+ * ... to compute statistics"): mu = R-bar W_Q mu_h, sigma = R-bar W_Q Sigma_h W_Q^T R-bar^T with
+ * mu_h, Sigma_h the mean and covariance of the buffered hidden states.
+ *   hidden [B, w, d_model], w_q [Hq, d, d_model] (row c of head g = the weights of query channel c),
+ *   both in p->dtype.  rope_layout, cov_ddof, horizon_T as for ea_query_stats; q_is_rotated is not
+ *   used (the projection of a hidden state carries no rotation yet). */
+ea_status ea_query_stats_hidden(const ea_params* p, const void* hidden, const void* w_q, int64_t d_model,
+                                int64_t window, const double* inv_freq, int64_t t_next, float* mu,
+                                float* sigma, void* ws, size_t ws_bytes, void* stream);
+
 /* Eq. 7-9 with ||v|| for ||W_o v|| (Sec. 3.1, implementation details) and the GQA group mean:
  *   l[g,i] = mu_g.k_i/sqrt(d) + k_i^T sigma_g k_i/(2d);  a[g,.] = softmax_i l[g,.];
  *   scores[h,i] = (mean_{g in group h} a[g,i] + epsilon) * ||v_i||_2.

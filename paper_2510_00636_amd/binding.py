@@ -45,6 +45,8 @@ def load_library():
     lib.ea_workspace_bytes.argtypes = [P, I64, I64]
     lib.ea_query_stats.restype = ctypes.c_int
     lib.ea_query_stats.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, VP, SZ, VP]
+    lib.ea_query_stats_hidden.restype = ctypes.c_int
+    lib.ea_query_stats_hidden.argtypes = [P, VP, VP, I64, I64, VP, I64, VP, VP, VP, SZ, VP]
     lib.ea_score.restype = ctypes.c_int
     lib.ea_score.argtypes = [P, VP, VP, I64, I64, VP, VP, VP, VP, SZ, VP]
     lib.ea_select.restype = ctypes.c_int
@@ -126,6 +128,13 @@ def query_stats(p, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, ws, strea
     _check(load_library().ea_query_stats(ctypes.byref(p), _ptr(q_win), int(window), int(q_pos0),
                                          _ptr(inv_freq), int(t_next), _ptr(mu), _ptr(sigma),
                                          _ptr(ws), _nbytes(ws), _stream(stream)), "ea_query_stats")
+
+
+def query_stats_hidden(p, hidden, w_q, d_model, window, inv_freq, t_next, mu, sigma, ws, stream=None):
+    _check(load_library().ea_query_stats_hidden(ctypes.byref(p), _ptr(hidden), _ptr(w_q), int(d_model),
+                                                int(window), _ptr(inv_freq), int(t_next), _ptr(mu),
+                                                _ptr(sigma), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "ea_query_stats_hidden")
 
 
 def score(p, k, v, n, n_cap, mu, sigma, scores, ws, stream=None):

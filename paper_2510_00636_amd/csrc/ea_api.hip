@@ -143,6 +143,28 @@ ea_status ea_query_stats(const ea_params* p, const void* q_win, int64_t window, 
                    (hipStream_t)stream);
 }
 
+ea_status ea_query_stats_hidden(const ea_params* p, const void* hidden, const void* w_q, int64_t d_model,
+                                int64_t window, const double* inv_freq, int64_t t_next, float* mu,
+                                float* sigma, void* ws, size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(hidden) || !aligned16(w_q) || !aligned16(mu) || !aligned16(sigma) || !inv_freq ||
+      ((uintptr_t)inv_freq & 7u))
+    return EA_ERR_INVALID_ARG;
+  if (window < 1 + d.ddof || t_next < 0 || d_model < 1 || d_model > (1 << 20)) return EA_ERR_INVALID_ARG;
+  if (window > kMaxWindow) return EA_ERR_UNSUPPORTED;
+  WsLayout L;
+  if ((s = check_ws(d, 1, window, ws, ws_bytes, &L)) != EA_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  float* q = (float*)((char*)ws + L.qproj);
+  EA_TRY(launch_project(d, hidden, w_q, (int)window, (int)d_model, q, st));
+  Dims dq = d;                       // the projected queries: fp32, not yet rotated
+  dq.dtype = EA_F32;
+  dq.q_is_rotated = 0;
+  return run_stats(dq, q, window, 0, inv_freq, t_next, mu, sigma, (char*)ws, L, st);
+}
+
 ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
                    const float* mu, const float* sigma, float* scores, void* ws, size_t ws_bytes,
                    void* stream) {

@@ -39,7 +39,7 @@ struct ScorePlan {
 };
 
 struct WsLayout {
-  size_t tab, mu, sigma, frags, post, logits, vnorm, part, lse, scores, idx, base, hist, blk, flags, total;
+  size_t tab, qproj, mu, sigma, frags, post, logits, vnorm, part, lse, scores, idx, base, hist, blk, flags, total;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

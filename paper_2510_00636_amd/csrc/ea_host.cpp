@@ -106,6 +106,7 @@ WsLayout make_ws_layout(const Dims& d, int64_t n, int64_t window) {
   const size_t qh = (size_t)d.qheads(), un = (size_t)d.units();
   ScorePlan sp = make_score_plan(d, n, 256);
   w.tab = take((size_t)window * d.half * 2 * sizeof(float));
+  w.qproj = take(qh * (size_t)window * d.D * sizeof(float));   // projected queries of ea_query_stats_hidden
   w.mu = take(qh * d.D * sizeof(float));
   w.sigma = take(qh * d.D * d.D * sizeof(float));
   w.frags = take(un * sp.passes * sp.nfrag * 1024);

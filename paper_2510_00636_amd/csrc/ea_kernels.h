@@ -57,6 +57,10 @@ hipError_t launch_split_pooled(const int32_t* flat, int B, int H, int64_t n, int
 hipError_t launch_compact_fill(const Dims& d, void* k, void* v, int64_t n, int64_t n_cap,
                                const int32_t* idx, int64_t n_keep, int32_t* perm, hipStream_t st);
 
+// ea_frontend.hip: q [B, Hq, w, d] fp32 = W_Q [Hq, d, dm] applied to hidden [B, w, dm] (dtype of d)
+hipError_t launch_project(const Dims& d, const void* hidden, const void* wq, int w, int dm, float* q,
+                          hipStream_t st);
+
 // ea_baselines.hip: scorer = ea_scorer; scratch: units * kBaselineChunks * D floats
 hipError_t launch_baseline(const Dims& d, int kind, const void* k, int64_t n, int64_t n_cap,
                            int64_t n_sink, float* scores, float* scratch, hipStream_t st);

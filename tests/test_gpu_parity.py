@@ -602,3 +602,33 @@ def test_select_adaptive_and_ragged_compaction(n, n_keep, floor):
             m = gl[b, h]
             assert np.array_equal(ko[b, h, :m], ref[b][h][0]) and np.array_equal(vo[b, h, :m], ref[b][h][1])
             assert np.array_equal(ko[b, h, m:], k[b, h, m:]) and np.array_equal(vo[b, h, m:], v[b, h, m:])
+
+
+# ------------------------------------------------------------------- hidden-state front end (Eq. 5 as printed)
+@pytest.mark.parametrize("dt,d,w,dm", [("bf16", 128, 128, 512), ("f32", 64, 40, 200), ("bf16", 256, 70, 96)])
+def test_query_stats_from_hidden_states(dt, d, w, dm):
+    """mu, Sigma from a hidden-state buffer and W_Q against the oracle's literal Eq. 5 (mean and
+    covariance of the hidden states, then W_Q, then R-bar)."""
+    import torch
+    from oracle import ea_extensions as X
+    from ea_inputs import bf16_bits_from_f64, inv_freq_table
+    cfg = (CONFIGS["c2"] if dt == "bf16" else CONFIGS["c1"]).with_(head_dim=d, n_q_heads=4, n_kv_heads=2, batch=2)
+    p = P.params_for(cfg)
+    r = np.random.default_rng(d + w + dm)
+    hidden = r.standard_normal((2, w, dm)) * 1.5 + r.standard_normal(dm)          # channels with offsets
+    w_q = r.standard_normal((4, d, dm)) / np.sqrt(dm)
+    if dt == "bf16":
+        hb, wb = bf16_bits_from_f64(hidden), bf16_bits_from_f64(w_q)
+        h64, w64 = widen(hb), widen(wb)
+    else:
+        hb, wb = hidden.astype(np.float32), w_q.astype(np.float32)
+        h64, w64 = hb.astype(np.float64), wb.astype(np.float64)
+    inv = inv_freq_table(d, cfg.rope_base)
+    t_next = 70000
+    ws = P.workspace(p, 8, w)
+    mu = torch.empty(2, 4, d, dtype=torch.float32, device="cuda")
+    sg = torch.empty(2, 4, d, d, dtype=torch.float32, device="cuda")
+    ea.query_stats_hidden(p, P.to_dev(hb), P.to_dev(wb), dm, w, P.to_dev(inv), t_next, mu, sg, ws)
+    torch.cuda.synchronize()
+    rmu, rsg = X.query_stats_hidden(h64, w64, inv, t_next, T=cfg.horizon_T)
+    P.check_stats(mu.cpu().numpy(), sg.cpu().numpy(), rmu, rsg)
