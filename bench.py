@@ -25,7 +25,7 @@ instrumented steps, `hbm_copy_ceiling_GBs` (a plain 2 GiB device copy on this bo
 `cpu_baseline` (the fp64 oracle timed on this machine's host cores on a sample of the same input).
 
     python bench.py [--steps K] [--warmup W] [--workload c3|c2|c4|c5] [--ratio R] [--layers L]
-                    [--streams S] [--layer-batch LB] [--ordered] [--graph]
+                    [--streams S] [--layer-batch LB] [--ordered] [--graph] [--skip-layer-by-layer]
 """
 import argparse
 import hashlib
@@ -59,6 +59,8 @@ def parse():
                     help="HIP streams the calls are spread over (each with its own workspace)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (all calls, one stream) in a HIP graph and time replays of it")
+    ap.add_argument("--skip-layer-by-layer", action="store_true",
+                    help="leave the layer-by-layer leg out (profiling runs: every launch then has one shape)")
     ap.add_argument("--ordered", action="store_true",
                     help="decode schedule: use the order-preserving compaction instead of the order-free one")
     return ap.parse_args()
@@ -232,11 +234,13 @@ def run_prefill(a, torch, ea, cfg):
     bytes_per_pair = 2 * d * 2 * (1 + 2 * f)                     # K,V read once + kept rows read+written
     frac = lambda ms: pairs * bytes_per_pair / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
-    lbl_times = timed(step_layer_by_layer, restore, max(2, min(a.steps, 3)), 1, torch)
-    lbl_ms = 1e3 * sum(lbl_times) / len(lbl_times)
-    layer_by_layer = {"ms_per_step": round(lbl_ms, 4), "value": round(pairs / (lbl_ms * 1e-3) / 1e9, 4),
-                      "unit": "G pairs/s", "path_hbm_frac": round(frac(lbl_ms), 4),
-                      "launch_shape": "1 layer per call, 1 stream"}
+    layer_by_layer = None
+    if not a.skip_layer_by_layer:
+        lbl_times = timed(step_layer_by_layer, restore, max(2, min(a.steps, 3)), 1, torch)
+        lbl_ms = 1e3 * sum(lbl_times) / len(lbl_times)
+        layer_by_layer = {"ms_per_step": round(lbl_ms, 4), "value": round(pairs / (lbl_ms * 1e-3) / 1e9, 4),
+                          "unit": "G pairs/s", "path_hbm_frac": round(frac(lbl_ms), 4),
+                          "launch_shape": "1 layer per call, 1 stream"}
 
     # ---- per-stage durations with HIP events on the launch stream (instrumented steps: the same
     #      calls as the timed steps, one after the other on one stream, so each kernel runs alone)

@@ -44,12 +44,15 @@ __global__ void k_rope_table(const double* __restrict__ inv_freq, long long q_po
 }
 
 // ---------------------------------------------------------------------------------------
-// One workgroup = 32 rows of one head's Sigma.  The window is read ONCE, in chunks of up to 64
-// samples: every thread issues all its 16-byte query loads and table loads of a chunk together
-// (one memory latency per chunk instead of one per sample; the next chunk's loads go out before
-// the current chunk's arithmetic), maps them to u~, subtracts the head's first sample u~_0 and
-// writes the result to LDS; the four wavefronts then add the chunk's outer products to their
-// 32 x 32 accumulator tiles with fp32 matrix-core instructions, two samples per instruction.
+// Sigma is symmetric, so only its 32 x 32 tiles on and above the diagonal are computed (3 of 4 at
+// d = 64, 10 of 16 at d = 128, 36 of 64 at d = 256) and every tile above the diagonal is stored
+// twice, once transposed.  A head's tiles are dealt to kStatsParts<D> workgroups (1 / 2 / 4), each
+// of which reads the window ONCE, in chunks of up to 64 samples: every thread issues all its
+// 16-byte query loads and table loads of a chunk together (one memory latency per chunk instead
+// of one per sample; the next chunk's loads go out before the current chunk's arithmetic), maps
+// them to u~, subtracts the head's first sample u~_0 and writes the result to LDS; the four
+// wavefronts then add the chunk's outer products to their accumulator tiles with fp32
+// matrix-core instructions, two samples per instruction.
 // With x = u~ - u~_0,
 //     mean  = u~_0 + (1/w) sum_s x_s
 //     Sigma = (1/(w - ddof)) (sum_s x_s x_s^T - w xbar xbar^T)
@@ -57,7 +60,21 @@ __global__ void k_rope_table(const double* __restrict__ inv_freq, long long q_po
 // term costs no accuracy even for channels whose mean is many standard deviations from zero.
 // Column sums are formed on the way in (each thread keeps the sums of the 16 channels of its
 // items, all of one channel group) and combined in a fixed order, so results are reproducible.
+// The fp32 matrix-core work is what bounds the kernel for long windows (64 cycles per pair of
+// samples and tile): the triangle and the even deal over workgroups are what keep it short.
 constexpr int kStatsWC = 64;    // samples per LDS chunk
+template <int D> struct StatsTiling {
+  static constexpr int NCT = D / 32;                       // 32-column tiles across Sigma
+  static constexpr int NT = NCT * (NCT + 1) / 2;           // tiles on and above the diagonal
+  static constexpr int PARTS = D <= 64 ? 1 : (D <= 128 ? 2 : 4);
+  static constexpr int TP = (NT + PARTS - 1) / PARTS;      // tiles per workgroup
+  // A workgroup's first 4 WHOLE tiles go one (or WHOLE) to each wavefront; the SHARED tiles left
+  // over are each split four ways by samples and the four partial tiles added at the end, so
+  // every wavefront carries the same matrix-core load.
+  static constexpr int WHOLE = TP >= 4 ? TP / 4 : 1;
+  static constexpr int SHARED = TP >= 4 ? TP % 4 : 0;
+  static constexpr int SLOTS = WHOLE + SHARED;             // accumulator tiles per wavefront
+};
 
 // Channels of pair e of channel group g: ja for the first, jb for the second element of the pair.
 template <int D>
@@ -127,35 +144,33 @@ __device__ __forceinline__ void stats_unpack_item(const StatsRaw<BF16>& raw, int
 }
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 
-// Register budget: three workgroups per CU at d <= 128 (168 registers), two at d = 256 (240),
-// without spills for bf16 input (prefetched items stay packed).  With the compiler's own choice
-// (184 / 356 registers: two / one workgroup per CU) the 640 workgroups of a decode-shape call
-// did not fit on the chip at once, and the d = 256 shape had nothing to overlap its staging
-// with: 25 -> 15 us and 74 -> 26 us per layer.  A budget met only by spilling is no use here: a
-// kernel that needs scratch memory costs some 10 us more per launch when several streams are
-// in use.
+// Register budget: three workgroups per CU at d <= 128 (168 registers), two at d = 256 (256),
+// without spills for bf16 input (prefetched items stay packed, u~_0 lives in LDS, the tile numbers
+// are scalar).  With more registers per wavefront the 640 workgroups of a decode-shape call do not
+// fit on the chip at once.  A budget met only by spilling is no use here: a kernel that needs
+// scratch memory costs some 10 us more per launch when several streams are in use.
 template <int D, bool BF16>
 __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* __restrict__ q_win, int w, int layout,
                                                int ddof, const float2* __restrict__ tab,
                                                float* __restrict__ mu, float* __restrict__ sigma) {
   constexpr int HALF = D / 2, G8 = HALF / 8;          // groups of 8 channel pairs per sample
   constexpr int ITEMS = kStatsWC * G8 / 256;          // (sample, group) items per thread and chunk
-  constexpr int NCT = D / 32;                         // 32-column tiles across Sigma
-  constexpr int TPW = (NCT + 3) / 4;                  // tiles per wavefront
+  typedef StatsTiling<D> TL;
+  constexpr int NCT = TL::NCT, TPW = TL::SLOTS;
   static_assert(256 % G8 == 0 && ITEMS >= 1, "one channel group per thread");
   extern __shared__ __align__(16) float s_dyn[];
   float* s_u = s_dyn;                                 // [kStatsWC][D]   x = u~ - u~_0 of the chunk
   float* s_part = s_dyn + kStatsWC * D;               // [4][D]          column sums per wavefront
   float* s_shift = s_part + 4 * D;                    // [D]             u~_0
   float* s_xbar = s_shift + D;                        // [D]             (1/w) sum_s x_s
-  const int head = blockIdx.x, rb = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int head = blockIdx.x, part = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave-uniform: tile numbers stay scalar
   const size_t qbase = (size_t)head * w * D;
   const int nchunks = (w + kStatsWC - 1) / kStatsWC;
   const int g = tid % G8;                             // the channel group of all this thread's items
 
-  // u~_0 for this thread's group
-  float sha[8], shb[8];
-  {
+  // u~_0 of the head, kept in LDS (every thread reads its own group's 16 values per item)
+  if (tid < G8) {
     float qa[8], qb[8];
     float2 tb[8];
     StatsRaw<BF16> raw0;
@@ -163,17 +178,11 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* _
     stats_unpack_item<BF16>(raw0, layout, qa, qb, tb);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      sha[e] = tb[e].x * qa[e] - tb[e].y * qb[e];
-      shb[e] = tb[e].y * qa[e] + tb[e].x * qb[e];
-    }
-    if (tid < G8) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        s_shift[stats_ja<D>(layout, g, e)] = sha[e];
-        s_shift[stats_jb<D>(layout, g, e)] = shb[e];
-      }
+      s_shift[stats_ja<D>(layout, g, e)] = tb[e].x * qa[e] - tb[e].y * qb[e];
+      s_shift[stats_jb<D>(layout, g, e)] = tb[e].y * qa[e] + tb[e].x * qb[e];
     }
   }
+  __syncthreads();
   float suma[8], sumb[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { suma[e] = 0.f; sumb[e] = 0.f; }
@@ -182,7 +191,21 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* _
   // time, the 32 x 32 block  x[rows] x[cols]^T.  Lane l feeds row (or column) l % 32 of sample
   // l / 32 of the pair; wavefront `wave` owns the column tiles wave, wave + 4, ...
   const int r32 = lane & 31, hh = lane >> 5;
-  const int i0 = rb * 32;
+  // this wavefront's tiles: number wave + 4 t of the workgroup's share for the whole ones, then the
+  // shared ones; rows of the triangle in order
+  int t_rb[TPW], t_ct[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    const int local = t < TL::WHOLE ? wave + 4 * t : 4 * TL::WHOLE + (t - TL::WHOLE);
+    int idx = part * TL::TP + local, rb = 0;
+    const bool ok = local < TL::TP && idx < TL::NT;
+    if (!ok) idx = 0;
+#pragma unroll
+    for (int r = 0; r < NCT; ++r)
+      if (idx >= NCT - rb && rb == r) { idx -= NCT - rb; ++rb; }
+    t_rb[t] = ok ? rb : -1;
+    t_ct[t] = rb + idx;
+  }
   floatx16_t acc[TPW];
 #pragma unroll
   for (int t = 0; t < TPW; ++t)
@@ -213,8 +236,8 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* _
         stats_unpack_item<BF16>(raw[it], layout, qa, qb, tb);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          xa[e] = tb[e].x * qa[e] - tb[e].y * qb[e] - sha[e];
-          xb[e] = tb[e].y * qa[e] + tb[e].x * qb[e] - shb[e];
+          xa[e] = tb[e].x * qa[e] - tb[e].y * qb[e] - s_shift[stats_ja<D>(layout, g, e)];
+          xb[e] = tb[e].y * qa[e] + tb[e].x * qb[e] - s_shift[stats_jb<D>(layout, g, e)];
           suma[e] += xa[e];
           sumb[e] += xb[e];
         }
@@ -234,27 +257,49 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* _
     }
     __syncthreads();
     if (ch + 1 < nchunks) load_chunk(ch + 1);         // in flight during the matrix-core loop
-    // four sample pairs per step: all their LDS reads first, then the MFMAs (samples past the
+    // a few sample pairs per step: all their LDS reads first, then the MFMAs (samples past the
     // chunk's end count as zero)
+    constexpr int PS = TPW == 1 ? 4 : 2;
     const int npair = (ns + 1) / 2;
-    for (int sp = 0; sp < npair; sp += 4) {
-      float av[4], bv[4][TPW];
+    for (int sp = 0; sp < npair; sp += PS) {
+      float av[PS][TPW], bv[PS][TPW];
+      const bool mine = ((sp / PS) & 3) == wave;       // this step's samples of the shared tiles
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < PS; ++u) {
         const int sl = 2 * (sp + u) + hh;
         const bool ok = sl < ns;
-        av[u] = ok ? s_u[sl * D + i0 + r32] : 0.f;
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
-          const int ct = wave + 4 * t;
-          bv[u][t] = (ok && ct < NCT) ? s_u[sl * D + ct * 32 + r32] : 0.f;
+          const bool okt = ok && t_rb[t] >= 0 && (t < TL::WHOLE || mine);
+          av[u][t] = okt ? s_u[sl * D + t_rb[t] * 32 + r32] : 0.f;
+          bv[u][t] = okt ? s_u[sl * D + t_ct[t] * 32 + r32] : 0.f;
         }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < PS; ++u)
 #pragma unroll
         for (int t = 0; t < TPW; ++t)
-          if (wave + 4 * t < NCT) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u][t], acc[t], 0, 0, 0);
+          if (t_rb[t] >= 0 && (t < TL::WHOLE || mine))
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][t], bv[u][t], acc[t], 0, 0, 0);
+    }
+  }
+  if (TL::SHARED > 0) {
+    // the four partial tiles of every shared tile, added in wavefront order by wavefront 0
+    static_assert(TL::SHARED * 4 * 16 * 64 <= kStatsWC * D, "partial tiles fit in the chunk buffer");
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < TL::SHARED; ++r)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_u[((r * 4 + wave) * 16 + v) * 64 + lane] = acc[TL::WHOLE + r][v];
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int r = 0; r < TL::SHARED; ++r)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float* pp = s_u + (r * 4 * 16 + v) * 64 + lane;
+          acc[TL::WHOLE + r][v] = (pp[0] + pp[16 * 64]) + (pp[2 * 16 * 64] + pp[3 * 16 * 64]);
+        }
     }
   }
 
@@ -279,21 +324,23 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* _
   for (int c = tid; c < D; c += 256) {
     const float xb = ((s_part[c] + s_part[D + c]) + (s_part[2 * D + c] + s_part[3 * D + c])) * invw;
     s_xbar[c] = xb;
-    if (rb == 0) mu[(size_t)head * D + c] = s_shift[c] + xb;
+    if (part == 0) mu[(size_t)head * D + c] = s_shift[c] + xb;
   }
   __syncthreads();
   // accumulator register v of lane (r32, hh) is row 8 (v / 4) + 4 hh + v % 4, column r32 of the tile
   const float fw = (float)w, inv = 1.0f / (float)(w - ddof);
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
-    const int ct = wave + 4 * t;
-    if (ct < NCT) {
-      const int j = ct * 32 + r32;
+    if (t_rb[t] >= 0 && (t < TL::WHOLE || wave == 0)) {
+      const int i0 = t_rb[t] * 32, j = t_ct[t] * 32 + r32;
+      const bool mirror = t_rb[t] != t_ct[t];
       const float xj = s_xbar[j];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int i = i0 + 8 * (v / 4) + 4 * hh + v % 4;
-        sigma[((size_t)head * D + i) * D + j] = (acc[t][v] - fw * s_xbar[i] * xj) * inv;
+        const float val = (acc[t][v] - fw * s_xbar[i] * xj) * inv;
+        sigma[((size_t)head * D + i) * D + j] = val;
+        if (mirror) sigma[((size_t)head * D + j) * D + i] = val;
       }
     }
   }
@@ -454,7 +501,7 @@ static hipError_t launch_stats_one(const Dims& d, const void* q_win, int w, cons
   static LdsOptIn opt;                    // one per kernel instance
   hipError_t e = opt.ensure(reinterpret_cast<const void*>(kern), lds);
   if (e != hipSuccess) return e;
-  dim3 grid(d.qheads(), D / 32);
+  dim3 grid(d.qheads(), StatsTiling<D>::PARTS);
   kern<<<grid, 256, lds, st>>>(q_win, w, d.rope_layout, d.ddof, tab, mu, sigma);
   return hipGetLastError();
 }
