@@ -78,8 +78,8 @@ ea_status ea_query_stats(const ea_params* p, const void* q_win, int64_t window, 
                          const double* inv_freq, int64_t t_next, float* mu, float* sigma,
                          void* ws, size_t ws_bytes, void* stream);
 
-/* Eq. 5-6 as printed, from a buffer of hidden states (Sec. 3.1: "a small buffer of hidden states
- * ... to compute statistics"): mu = R-bar W_Q mu_h, sigma = R-bar W_Q Sigma_h W_Q^T R-bar^T with
+/* Eq. 5-6 as printed, from the buffer of recent hidden states that the decoding set-up of
+ * Sec. 3.1 keeps for the statistics: mu = R-bar W_Q mu_h, sigma = R-bar W_Q Sigma_h W_Q^T R-bar^T with
  * mu_h, Sigma_h the mean and covariance of the buffered hidden states.
  *   hidden [B, w, d_model], w_q [Hq, d, d_model] (row c of head g = the weights of query channel c),
  *   both in p->dtype.  rope_layout, cov_ddof, horizon_T as for ea_query_stats; q_is_rotated is not
@@ -97,6 +97,26 @@ ea_status ea_query_stats_hidden(const ea_params* p, const void* hidden, const vo
 ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
                    const float* mu, const float* sigma, float* scores,
                    void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 9 as printed, with the output projection: ||W_o v|| in place of ||v||.  Query head g sends the
+ * value head of its group through its own d columns of W_o, so
+ *   scores[h,i] = (1/G) sum_{g in group h} (a[g,i] + epsilon) * ||W_o^(g) v_i||_2 .
+ * The norm is sqrt(v^T M_g v) with M_g = W_o^(g)^T W_o^(g), a quadratic form like Eq. 7's:
+ *   ea_wo_gram         gram [Hq, d, d] fp32 (out) from w_o [Hq, d_model, d] in p->dtype (row m of head
+ *                      g = the weights that take head g's d channels to output channel m).  Depends on
+ *                      the weights only: once per layer.  p->batch is not used.
+ *   ea_value_norms_wo  wnorm [B, Hq, n] fp32 (out) = ||W_o^(g) v_i|| for the value rows < n of the
+ *                      head's group; reads v once per pass of the score kernel.  Values do not
+ *                      change while they are cached, so a caller may keep wnorm across compress
+ *                      passes and compact it with the cache.
+ *   ea_score_wo        ea_score with wnorm [B, Hq, n] in place of ||v||.
+ * Errors as for ea_score; 1 <= d_model <= 2^20. */
+ea_status ea_wo_gram(const ea_params* p, const void* w_o, int64_t d_model, float* gram, void* stream);
+ea_status ea_value_norms_wo(const ea_params* p, const void* v, int64_t n, int64_t n_cap, const float* gram,
+                            float* wnorm, void* ws, size_t ws_bytes, void* stream);
+ea_status ea_score_wo(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
+                      const float* mu, const float* sigma, const float* wnorm, float* scores,
+                      void* ws, size_t ws_bytes, void* stream);
 
 /* Sec. 2.2 "Compression", Listing 1 top-k: per KV head the n_keep pairs of highest score,
  * equal scores going to the lower position; idx is written in ascending position order.

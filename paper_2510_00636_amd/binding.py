@@ -51,6 +51,12 @@ def load_library():
     lib.ea_score.argtypes = [P, VP, VP, I64, I64, VP, VP, VP, VP, SZ, VP]
     lib.ea_select.restype = ctypes.c_int
     lib.ea_select.argtypes = [P, VP, I64, I64, VP, VP, SZ, VP]
+    lib.ea_wo_gram.restype = ctypes.c_int
+    lib.ea_wo_gram.argtypes = [P, VP, I64, VP, VP]
+    lib.ea_value_norms_wo.restype = ctypes.c_int
+    lib.ea_value_norms_wo.argtypes = [P, VP, I64, I64, VP, VP, VP, SZ, VP]
+    lib.ea_score_wo.restype = ctypes.c_int
+    lib.ea_score_wo.argtypes = [P, VP, VP, I64, I64, VP, VP, VP, VP, VP, SZ, VP]
     lib.ea_select_static.restype = ctypes.c_int
     lib.ea_select_static.argtypes = [P, VP, I64, I64, VP, VP]
     lib.ea_compact.restype = ctypes.c_int
@@ -135,6 +141,23 @@ def query_stats_hidden(p, hidden, w_q, d_model, window, inv_freq, t_next, mu, si
                                                 int(window), _ptr(inv_freq), int(t_next), _ptr(mu),
                                                 _ptr(sigma), _ptr(ws), _nbytes(ws), _stream(stream)),
            "ea_query_stats_hidden")
+
+
+def wo_gram(p, w_o, d_model, gram, stream=None):
+    _check(load_library().ea_wo_gram(ctypes.byref(p), _ptr(w_o), int(d_model), _ptr(gram), _stream(stream)),
+           "ea_wo_gram")
+
+
+def value_norms_wo(p, v, n, n_cap, gram, wnorm, ws, stream=None):
+    _check(load_library().ea_value_norms_wo(ctypes.byref(p), _ptr(v), int(n), int(n_cap), _ptr(gram),
+                                            _ptr(wnorm), _ptr(ws), _nbytes(ws), _stream(stream)),
+           "ea_value_norms_wo")
+
+
+def score_wo(p, k, v, n, n_cap, mu, sigma, wnorm, scores, ws, stream=None):
+    _check(load_library().ea_score_wo(ctypes.byref(p), _ptr(k), _ptr(v), int(n), int(n_cap), _ptr(mu),
+                                      _ptr(sigma), _ptr(wnorm), _ptr(scores), _ptr(ws), _nbytes(ws),
+                                      _stream(stream)), "ea_score_wo")
 
 
 def score(p, k, v, n, n_cap, mu, sigma, scores, ws, stream=None):

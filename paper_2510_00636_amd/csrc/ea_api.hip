@@ -57,7 +57,9 @@ static ea_status run_stats(const Dims& d, const void* q_win, int64_t window, int
 static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                            const float* mu, const float* sigma, float* scores, uint32_t* hist0,
                            bool hist_zeroed, char* ws, const WsLayout& L, hipStream_t st,
-                           hipEvent_t* ev = nullptr) {
+                           hipEvent_t* ev = nullptr, const float* wnorm = nullptr, float* wnorm_out = nullptr) {
+  // wnorm: Eq. 9 with per-query-head norms ||W_o v||.  wnorm_out: stop after pass A and turn its
+  // quadratic forms into such norms (the caller passed the values as keys, mu = 0, Sigma = M_g).
   float* vnorm = (float*)(ws + L.vnorm);
   uint32_t* hist = (uint32_t*)(ws + L.hist);
   if (d.dtype == EA_BF16 && !hist_zeroed) EA_TRY(launch_zero(hist, (size_t)d.units() * 3 * kSelBins, st));
@@ -71,16 +73,20 @@ static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t 
                              (float2*)(ws + L.part), hist + 2 * kSelBins + kTicketSlot, 3 * kSelBins,
                              st));
     if (ev) EA_TRY(hipEventRecord(ev[1], st));
+    if (wnorm_out) return launch_wnorm(ws + L.logits, 0, (size_t)d.qheads() * n, d.D, wnorm_out, st) == hipSuccess
+                              ? EA_OK : EA_ERR_DEVICE;
     EA_TRY(launch_finalize(d, n, ws + L.logits, 0, vnorm, ws + L.part, sp.npart, ws + L.lse, scores,
-                           hist0, st));
+                           hist0, st, wnorm));
   } else {
     int nchunk = 0;
     if (ev) EA_TRY(hipEventRecord(ev[0], st));
     EA_TRY(launch_score_f32(d, k, v, n, n_cap, mu, sigma, (double*)(ws + L.logits), vnorm,
                             (double2*)(ws + L.part), &nchunk, st));
     if (ev) EA_TRY(hipEventRecord(ev[1], st));
+    if (wnorm_out) return launch_wnorm(ws + L.logits, 1, (size_t)d.qheads() * n, d.D, wnorm_out, st) == hipSuccess
+                              ? EA_OK : EA_ERR_DEVICE;
     EA_TRY(launch_finalize(d, n, ws + L.logits, 1, vnorm, ws + L.part, nchunk, ws + L.lse, scores,
-                           hist0, st));
+                           hist0, st, wnorm));
   }
   return EA_OK;
 }
@@ -178,6 +184,52 @@ ea_status ea_score(const ea_params* p, const void* k, const void* v, int64_t n, 
   if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
   return run_score(d, k, v, n, n_cap, mu, sigma, scores, nullptr, false, (char*)ws, L,
                    (hipStream_t)stream);
+}
+
+ea_status ea_wo_gram(const ea_params* p, const void* w_o, int64_t d_model, float* gram, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(w_o) || !aligned16(gram) || d_model < 1 || d_model > (1 << 20)) return EA_ERR_INVALID_ARG;
+  EA_TRY(launch_gram(d, w_o, (int)d_model, gram, (hipStream_t)stream));
+  return EA_OK;
+}
+
+ea_status ea_value_norms_wo(const ea_params* p, const void* v, int64_t n, int64_t n_cap, const float* gram,
+                            float* wnorm, void* ws, size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(v) || !aligned16(gram) || !aligned16(wnorm)) return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > kMaxN) return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  // pass A over the value rows with mu = 0 and Sigma = M_g (the same M for every sequence)
+  float* mu0 = (float*)((char*)ws + L.mu);
+  float* sg = (float*)((char*)ws + L.sigma);
+  EA_TRY(launch_zero((uint32_t*)mu0, (size_t)d.qheads() * d.D, st));
+  const size_t per_b = (size_t)d.Hq * d.D * d.D * sizeof(float);
+  for (int b = 0; b < d.B; ++b)
+    EA_TRY(hipMemcpyAsync((char*)sg + b * per_b, gram, per_b, hipMemcpyDeviceToDevice, st));
+  return run_score(d, v, v, n, n_cap, mu0, sg, nullptr, nullptr, false, (char*)ws, L, st, nullptr, nullptr,
+                   wnorm);
+}
+
+ea_status ea_score_wo(const ea_params* p, const void* k, const void* v, int64_t n, int64_t n_cap,
+                      const float* mu, const float* sigma, const float* wnorm, float* scores, void* ws,
+                      size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(mu) || !aligned16(sigma) || !aligned16(scores) ||
+      !aligned16(wnorm))
+    return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > kMaxN) return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  return run_score(d, k, v, n, n_cap, mu, sigma, scores, nullptr, false, (char*)ws, L,
+                   (hipStream_t)stream, nullptr, wnorm);
 }
 
 ea_status ea_select(const ea_params* p, const float* scores, int64_t n, int64_t n_keep, int32_t* idx,

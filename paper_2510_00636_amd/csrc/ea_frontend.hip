@@ -53,6 +53,47 @@ __global__ __launch_bounds__(256) void k_project(const void* __restrict__ hidden
   }
 }
 
+// Eq. 9 as printed weighs a pair by ||W_o v||.  With M_g = W_o^(g)^T W_o^(g) (d x d, from the d
+// columns of W_o that query head g feeds) that norm is sqrt(v^T M_g v): a quadratic form of the
+// same shape as Eq. 7's, so the score kernels evaluate it.  M_g depends on the weights only and is
+// formed once per layer: one workgroup = a 32 x 32 tile of one head's M, the d_model axis through
+// LDS 32 rows at a time, fp32 accumulation in row order.
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_gram(const void* __restrict__ wo, int dm, int D, float* __restrict__ gram) {
+  __shared__ float s_a[32][33], s_b[32][33];
+  const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
+  const int a0 = blockIdx.x * 32, b0 = blockIdx.y * 32, g = blockIdx.z;
+  const size_t base = (size_t)g * dm * D;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int m0 = 0; m0 < dm; m0 += 32) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = m0 + ty + 8 * i;
+      s_a[ty + 8 * i][tx] = m < dm ? load_elem<BF16>(wo, base + (size_t)m * D + a0 + tx) : 0.f;
+      s_b[ty + 8 * i][tx] = m < dm ? load_elem<BF16>(wo, base + (size_t)m * D + b0 + tx) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int m = 0; m < 32; ++m) {
+      const float bv = s_b[m][tx];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = fmaf(s_a[m][ty + 8 * i], bv, acc[i]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) gram[((size_t)g * D + a0 + ty + 8 * i) * D + b0 + tx] = acc[i];
+}
+
+hipError_t launch_gram(const Dims& d, const void* w_o, int dm, float* gram, hipStream_t st) {
+  dim3 grid(d.D / 32, d.D / 32, d.Hq);
+  if (d.dtype == EA_BF16)
+    k_gram<true><<<grid, 256, 0, st>>>(w_o, dm, d.D, gram);
+  else
+    k_gram<false><<<grid, 256, 0, st>>>(w_o, dm, d.D, gram);
+  return hipGetLastError();
+}
+
 hipError_t launch_project(const Dims& d, const void* hidden, const void* wq, int w, int dm, float* q,
                           hipStream_t st) {
   dim3 grid((w + 31) / 32, d.D / 32, d.qheads());

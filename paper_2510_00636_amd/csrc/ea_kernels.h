@@ -28,7 +28,9 @@ hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t
 // one LT per query head (used when a head has too many partials to reduce inside pass B)
 hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
                            const float* vnorm, const void* part, int npart, void* lse, float* scores,
-                           uint32_t* hist0, hipStream_t st);
+                           uint32_t* hist0, hipStream_t st, const float* wnorm = nullptr);
+// wnorm[i] = sqrt(max(2 d logits[i], 0)) for i < count
+hipError_t launch_wnorm(const void* logits, int logits_f64, size_t count, int D, float* wnorm, hipStream_t st);
 
 // ea_select.hip
 // heads this short are selected by one workgroup per unit out of LDS, in one launch (no global
@@ -60,6 +62,8 @@ hipError_t launch_compact_fill(const Dims& d, void* k, void* v, int64_t n, int64
 // ea_frontend.hip: q [B, Hq, w, d] fp32 = W_Q [Hq, d, dm] applied to hidden [B, w, dm] (dtype of d)
 hipError_t launch_project(const Dims& d, const void* hidden, const void* wq, int w, int dm, float* q,
                           hipStream_t st);
+// gram[g] = W_o^(g)^T W_o^(g) for w_o [Hq, dm, D] in the cache dtype
+hipError_t launch_gram(const Dims& d, const void* w_o, int dm, float* gram, hipStream_t st);
 
 // ea_baselines.hip: scorer = ea_scorer; scratch: units * kBaselineChunks * D floats
 hipError_t launch_baseline(const Dims& d, int kind, const void* k, int64_t n, int64_t n_cap,

@@ -229,7 +229,8 @@ __global__ __launch_bounds__(256) void k_finalize(const LT* __restrict__ logits,
                                                   const LT* __restrict__ lse_in, int G, int npart,
                                                   long long n, float eps, int units, int rounds,
                                                   float* __restrict__ scores,
-                                                  uint32_t* __restrict__ hist0) {
+                                                  uint32_t* __restrict__ hist0,
+                                                  const float* __restrict__ wnorm) {
   __shared__ LT s_lse[64];
   __shared__ uint32_t s_hist[kSelBins];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -264,14 +265,20 @@ __global__ __launch_bounds__(256) void k_finalize(const LT* __restrict__ logits,
       LT lv[4];
 #pragma unroll
       for (int it = 0; it < 4; ++it) lv[it] = lp[ic[it]];
+      if (wnorm) {        // Eq. 9 with the output projection: every query head weighs by its own norm
+        const float* wp = wnorm + ((size_t)unit * G + g) * n;
 #pragma unroll
-      for (int it = 0; it < 4; ++it) acc[it] += ea_exp(lv[it] - lse);
+        for (int it = 0; it < 4; ++it) acc[it] += (ea_exp(lv[it] - lse) + (LT)eps) * (LT)wp[ic[it]];
+      } else {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) acc[it] += ea_exp(lv[it] - lse);
+      }
     }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const long long i = base + it * 256 + tid;
       if (i < n) {
-        float sc = (float)((acc[it] * invG + (LT)eps) * (LT)vn[it]);
+        float sc = wnorm ? (float)(acc[it] * invG) : (float)((acc[it] * invG + (LT)eps) * (LT)vn[it]);
         scores[(size_t)unit * n + i] = sc;
         if (hist0) {
           atomicAdd(&s_hist[__float_as_uint(sc) >> 21], 1u);
@@ -290,11 +297,31 @@ __global__ __launch_bounds__(256) void k_finalize(const LT* __restrict__ logits,
   }
 }
 
+// ||W_o^(g) v_i|| from the quadratic form pass A leaves in `logits` when it is run over the value
+// rows with mu = 0 and Sigma = M_g = W_o^(g)^T W_o^(g):  logits = v^T M_g v / (2 d).
+template <typename LT>
+__global__ void k_wnorm(const LT* __restrict__ logits, size_t count, float two_d, float* __restrict__ wnorm) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) {
+    const LT q = logits[i] * (LT)two_d;
+    wnorm[i] = q > (LT)0 ? (float)sqrt(q) : 0.f;
+  }
+}
+
+hipError_t launch_wnorm(const void* logits, int logits_f64, size_t count, int D, float* wnorm, hipStream_t st) {
+  const unsigned grid = (unsigned)((count + 255) / 256);
+  if (logits_f64)
+    k_wnorm<double><<<grid, 256, 0, st>>>((const double*)logits, count, 2.0f * (float)D, wnorm);
+  else
+    k_wnorm<float><<<grid, 256, 0, st>>>((const float*)logits, count, 2.0f * (float)D, wnorm);
+  return hipGetLastError();
+}
+
 constexpr int kLseInlineMax = 4096;   // more partials per head than this: reduce them in k_lse first
 
 hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
                            const float* vnorm, const void* part, int npart, void* lse, float* scores,
-                           uint32_t* hist0, hipStream_t st) {
+                           uint32_t* hist0, hipStream_t st, const float* wnorm) {
   const int rounds = n > 32768 ? 4 : 1;
   const int64_t nblk = (n + 1024 * rounds - 1) / (1024 * rounds);
   const unsigned grid = (unsigned)(nblk * d.units());
@@ -303,12 +330,12 @@ hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int log
     if (pre) k_lse<double><<<d.qheads(), 256, 0, st>>>((const double2*)part, npart, (double*)lse);
     k_finalize<double><<<grid, 256, 0, st>>>((const double*)logits, vnorm, (const double2*)part,
                                              pre ? (const double*)lse : nullptr, d.G, npart, n, d.eps,
-                                             d.units(), rounds, scores, hist0);
+                                             d.units(), rounds, scores, hist0, wnorm);
   } else {
     if (pre) k_lse<float><<<d.qheads(), 256, 0, st>>>((const float2*)part, npart, (float*)lse);
     k_finalize<float><<<grid, 256, 0, st>>>((const float*)logits, vnorm, (const float2*)part,
                                             pre ? (const float*)lse : nullptr, d.G, npart, n, d.eps,
-                                            d.units(), rounds, scores, hist0);
+                                            d.units(), rounds, scores, hist0, wnorm);
   }
   return hipGetLastError();
 }

@@ -98,6 +98,13 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.ea_select_static(byref(p), VP(ok), (1 << 20) + 1, 4, VP(ok), None) == 2
     assert lib.ea_select_static(byref(p), VP(ok), 8, 9, VP(ok), None) == 1
     assert lib.ea_select_static(byref(p), VP(ok), 8, 0, None, None) == 0
+    # scores with the output projection: d_model range, null norms, n > n_cap, workspace
+    assert lib.ea_wo_gram(byref(p), VP(ok), 0, VP(ok), None) == 1
+    assert lib.ea_wo_gram(byref(p), VP(ok), (1 << 20) + 1, VP(ok), None) == 1
+    assert lib.ea_wo_gram(byref(p), None, 64, VP(ok), None) == 1
+    assert lib.ea_value_norms_wo(byref(p), VP(ok), 9, 8, VP(ok), VP(ok), VP(ok), 1 << 30, None) == 1
+    assert lib.ea_value_norms_wo(byref(p), VP(ok), 8, 8, VP(ok), VP(ok), VP(ok), 16, None) == 3
+    assert lib.ea_score_wo(byref(p), VP(ok), VP(ok), 8, 8, VP(ok), VP(ok), None, VP(ok), VP(ok), 1 << 30, None) == 1
     # n_keep == 0 is a valid no-op (returns before any launch)
     assert lib.ea_select(byref(p), VP(ok), 8, 0, None, VP(ok), 1 << 30, None) == 0
     assert lib.ea_compact(byref(p), VP(ok), VP(2 * ok), 8, 8, None, 0, VP(ok), VP(2 * ok), VP(ok), 1 << 30, None) == 0

@@ -632,3 +632,44 @@ def test_query_stats_from_hidden_states(dt, d, w, dm):
     torch.cuda.synchronize()
     rmu, rsg = X.query_stats_hidden(h64, w64, inv, t_next, T=cfg.horizon_T)
     P.check_stats(mu.cpu().numpy(), sg.cpu().numpy(), rmu, rsg)
+
+
+# ------------------------------------------------------------------- Eq. 9 as printed: ||W_o v||
+@pytest.mark.parametrize("dt,d,hq,hkv,n,dm", [("bf16", 128, 8, 2, 3000, 256), ("bf16", 128, 5, 1, 700, 96),
+                                              ("bf16", 64, 4, 2, 1100, 130), ("bf16", 256, 2, 1, 900, 64),
+                                              ("f32", 64, 4, 2, 500, 72)])
+def test_scores_with_output_projection(dt, d, hq, hkv, n, dm):
+    """ea_wo_gram + ea_value_norms_wo + ea_score_wo against the oracle's explicit W_o v products."""
+    import torch
+    from oracle import ea_extensions as X
+    from ea_inputs import bf16_bits_from_f64
+    cfg = (CONFIGS["c2"] if dt == "bf16" else CONFIGS["c1"]).with_(head_dim=d, n_q_heads=hq, n_kv_heads=hkv, batch=2)
+    lay = make_layer(cfg, n=n, window=16)
+    p = P.params_for(cfg, epsilon=0.02)
+    rmu, rsg = _oracle_stats(cfg, lay)
+    mu32, sg32 = rmu.astype(np.float32), rsg.astype(np.float32)
+    r = np.random.default_rng(n + dm)
+    w_o = r.standard_normal((hq, dm, d)) / np.sqrt(d) * (1.0 + np.arange(hq))[:, None, None]
+    if dt == "bf16":
+        wb = bf16_bits_from_f64(w_o)
+        w64 = widen(wb)
+    else:
+        wb = w_o.astype(np.float32)
+        w64 = wb.astype(np.float64)
+    ws = P.workspace(p, n, 16)
+    gram = torch.empty(hq, d, d, dtype=torch.float32, device="cuda")
+    wnorm = torch.empty(2, hq, n, dtype=torch.float32, device="cuda")
+    scores = torch.empty(2, hkv, n, dtype=torch.float32, device="cuda")
+    kd, vd = P.to_dev(lay["k"]), P.to_dev(lay["v"])
+    ea.wo_gram(p, P.to_dev(wb), dm, gram)
+    ea.value_norms_wo(p, vd, n, n, gram, wnorm, ws)
+    ea.score_wo(p, kd, vd, n, n, P.to_dev(mu32), P.to_dev(sg32), wnorm, scores, ws)
+    torch.cuda.synchronize()
+    g_ref = np.einsum("gma,gmb->gab", w64, w64)
+    got_g = gram.cpu().numpy().astype(np.float64)
+    assert np.abs(got_g - g_ref).max() <= 1e-5 * np.abs(g_ref).max()
+    wn_ref = X.wo_value_norms(widen(lay["v"]), w64)
+    tol = TOL[cfg.dtype]
+    P.check_scores(wnorm.cpu().numpy(), wn_ref, tol)
+    ref = X.scores_wo(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), sg32.astype(np.float64), w64, 0.02)
+    P.check_scores(scores.cpu().numpy(), ref, 2 * tol)
