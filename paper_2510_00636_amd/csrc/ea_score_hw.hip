@@ -280,7 +280,8 @@ __global__ __launch_bounds__(256, 2) void k_score_hw(ScoreArgs a) {
       if constexpr (f == 18 || f == 21) {
         constexpr int jx = f == 18 ? 0 : 1;
         const half8 t = Kx[jx] * (_Float16)0.0625f;
-        sq[jx] = t * t;
+        // saturate instead of overflowing for |k| > 4096: infinity times a zero residual is NaN
+        sq[jx] = __builtin_elementwise_min(t * t, (half8)(_Float16)65504.0f);
       }
       if constexpr (f == 19) dot8(C1{}, C0{}, acc1);
       if constexpr (f == 20) dot8(C1{}, C1{}, acc1);

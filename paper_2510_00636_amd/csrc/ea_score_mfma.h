@@ -399,7 +399,9 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
             ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Kh[f], f == 0 ? zero : ex, 0, 0, 0);
           } else if constexpr (f < NX) {
             half8 t = Kh[f - NKS] * (_Float16)0.0625f;
-            t = t * t;
+            // |k| > 4096 would square to infinity (and infinity times a zero residual is NaN): the
+            // correction saturates there instead, an error far below the rounding it corrects
+            t = __builtin_elementwise_min(t * t, (half8)(_Float16)65504.0f);
             ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, t, ex, 0, 0, 0);
           } else {
             constexpr int m = f - NX, g = m / NF, rem = m % NF;

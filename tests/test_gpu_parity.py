@@ -132,6 +132,36 @@ def test_score_zero_covariance_and_zero_mean():
     P.check_scores(got0, (1.0 / 600 + 0.02) * vn, 2e-3)
 
 
+@pytest.mark.parametrize("d,hq,hkv,n,kscale,decades", [(128, 8, 2, 5000, 1e3, 3), (128, 4, 1, 3000, 3e3, 5),
+                                                       (64, 4, 2, 2000, 300.0, 4), (256, 2, 1, 1500, 1e3, 3),
+                                                       (128, 4, 1, 3000, 1.0, 6)])
+def test_score_large_keys_and_wide_range_sigma(d, hq, hkv, n, kscale, decades):
+    """Keys of magnitude 1e3 (entries beyond 4096, where the squared keys of the diagonal
+    correction leave fp16 range) and a covariance whose diagonal spans several decades, scaled so
+    that the logits stay within a few tens."""
+    import torch
+    from ea_inputs import bf16_bits_from_f64
+    r = np.random.default_rng(d + n)
+    cfg = CONFIGS["c2"].with_(head_dim=d, n_q_heads=hq, n_kv_heads=hkv, batch=1)
+    p = P.params_for(cfg, epsilon=0.02)
+    sig_c = 10.0 ** (-decades * r.permutation(d) / d)
+    s = np.sqrt(5.0 * 2 * d / (kscale ** 2 * (sig_c ** 2).sum()))
+    q = (r.standard_normal((1, hq, 64, d)) + 0.3) * sig_c * s
+    mu = q.mean(axis=2)
+    c = q - mu[:, :, None]
+    mu32 = mu.astype(np.float32)
+    sg32 = (np.einsum("bgsi,bgsj->bgij", c, c) / 64).astype(np.float32)
+    kb = bf16_bits_from_f64(r.standard_normal((1, hkv, n, d)) * kscale)
+    vb = bf16_bits_from_f64(r.standard_normal((1, hkv, n, d)))
+    assert np.abs(widen(kb)).max() > (4096 if kscale >= 1e3 else 0)
+    ws = P.workspace(p, n, 64)
+    sc = torch.empty(1, hkv, n, dtype=torch.float32, device="cuda")
+    ea.score(p, P.to_dev(kb), P.to_dev(vb), n, n, P.to_dev(mu32), P.to_dev(sg32), sc, ws)
+    torch.cuda.synchronize()
+    ref = O.scores(widen(kb), widen(vb), mu32.astype(np.float64), sg32.astype(np.float64), 0.02)
+    P.check_scores(sc.cpu().numpy(), ref, 2e-3)
+
+
 def test_score_c2_full_size():
     cfg = CONFIGS["c2"]
     lay = make_layer(cfg)
