@@ -322,7 +322,9 @@ constexpr int kLseInlineMax = 4096;   // more partials per head than this: reduc
 hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
                            const float* vnorm, const void* part, int npart, void* lse, float* scores,
                            uint32_t* hist0, hipStream_t st, const float* wnorm) {
-  const int rounds = n > 32768 ? 4 : 1;
+  // 1024 keys per workgroup; four rounds of them (fewer histogram flushes) once that still leaves
+  // a few thousand workgroups: the pass is bound by memory latency and wants the chip full
+  const int rounds = (n + 1023) / 1024 * d.units() >= 4096 ? 4 : 1;
   const int64_t nblk = (n + 1024 * rounds - 1) / (1024 * rounds);
   const unsigned grid = (unsigned)(nblk * d.units());
   const bool pre = npart > kLseInlineMax;

@@ -169,6 +169,19 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* _
   const int nchunks = (w + kStatsWC - 1) / kStatsWC;
   const int g = tid % G8;                             // the channel group of all this thread's items
 
+  // the first chunk's loads go out before anything waits on memory
+  StatsRaw<BF16> raw[ITEMS];
+  auto load_chunk = [&](int ch) __attribute__((always_inline)) {
+    const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int sl = (tid + it * 256) / G8;
+      if (sl < ns)
+        stats_fetch_item<D, BF16>(q_win, qbase + (size_t)(s0 + sl) * D, g, layout,
+                                  tab + (size_t)(s0 + sl) * HALF, raw[it]);
+    }
+  };
+  load_chunk(0);
   // u~_0 of the head, kept in LDS (every thread reads its own group's 16 values per item)
   if (tid < G8) {
     float qa[8], qb[8];
@@ -212,18 +225,6 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* _
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
 
-  StatsRaw<BF16> raw[ITEMS];
-  auto load_chunk = [&](int ch) __attribute__((always_inline)) {
-    const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
-#pragma unroll
-    for (int it = 0; it < ITEMS; ++it) {
-      const int sl = (tid + it * 256) / G8;
-      if (sl < ns)
-        stats_fetch_item<D, BF16>(q_win, qbase + (size_t)(s0 + sl) * D, g, layout,
-                                  tab + (size_t)(s0 + sl) * HALF, raw[it]);
-    }
-  };
-  load_chunk(0);
   for (int ch = 0; ch < nchunks; ++ch) {
     const int s0 = ch * kStatsWC, ns = min(kStatsWC, w - s0);
     if (ch > 0) __syncthreads();                      // the previous chunk has been consumed
