@@ -39,7 +39,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published peak
 MFMA_F16_PEAK_TFLOPS = 2500.0
-SCORE_SOURCES = ("ea_score_hw.hip", "ea_score_mfma.h")
+SCORE_SOURCES = ("ea_score_hw.hip", "ea_score_mfma.h", "ea_score.hip", "ea_host.cpp")
 
 
 def parse():

@@ -41,9 +41,12 @@ ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
   ScorePlan s;
   s.hw = 0;
   s.tpt = 1;
-  if (d.D == 128 && d.dtype == EA_BF16 && d.G % 4 == 0 && n >= 2048) {
-    // groups of four query heads at d = 128: fragments in registers, one wavefront per head,
-    // two workgroups of four wavefronts per CU
+  if (d.D == 128 && d.dtype == EA_BF16 && d.G % 4 == 0 && n >= 2048 && (int64_t)d.units() * (d.G / 4) <= 8) {
+    // groups of four query heads at d = 128, calls of up to 8 (KV head, group) units: fragments in
+    // registers, one wavefront per head, two workgroups of four wavefronts per CU.  Measured per
+    // layer of 8 KV heads x 131072 keys: 128 us against 129 us for the LDS-fragment kernel and a
+    // cheaper finalize pass (coarser partials) when a call holds one layer; with two or more
+    // layers per call the LDS-fragment kernel is the faster one (115 against 121 us).
     s.hw = 1;
     s.GH = 4;
     s.passes = d.G / 4;
