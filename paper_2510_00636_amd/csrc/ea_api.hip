@@ -76,7 +76,7 @@ static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t 
     if (wnorm_out) return launch_wnorm(ws + L.logits, 0, (size_t)d.qheads() * n, d.D, wnorm_out, st) == hipSuccess
                               ? EA_OK : EA_ERR_DEVICE;
     EA_TRY(launch_finalize(d, n, ws + L.logits, 0, vnorm, ws + L.part, sp.npart, ws + L.lse, scores,
-                           hist0, st, wnorm));
+                           hist0, st, wnorm, sp.lse_pass));
   } else {
     int nchunk = 0;
     if (ev) EA_TRY(hipEventRecord(ev[0], st));

@@ -12,6 +12,7 @@ constexpr int kMaxWindow = 4096;
 constexpr int64_t kMaxN = (int64_t)1 << 26;   // cached rows per head the launch grids cover
 constexpr int kSelBins = 2048;        // radix-select digit width: 11 + 11 + 10 bits
 constexpr int kSelBlock = 4096;       // scores per workgroup in the select passes
+constexpr int kLseBlock = 2048;       // keys per softmax partial when the partials are taken from the stored logits
 constexpr int kCompactRows = 96;     // destination rows per workgroup chunk in ea_compact (not a power of two on purpose)
 
 struct Dims {
@@ -35,6 +36,7 @@ struct ScorePlan {
   int tpt;      // that kernel: tiles of 32 keys per ticket (1 or 4)
   int pg;       // keys per softmax partial (max, sum exp): partial j covers keys [j*pg, (j+1)*pg)
   int npart;    // partials per query head = ceil(n / pg)
+  int lse_pass; // 1: pass A leaves only logits; the partials are taken from them by a pass of their own
   size_t lds_bytes;
 };
 

@@ -41,6 +41,7 @@ ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
   ScorePlan s;
   s.hw = 0;
   s.tpt = 1;
+  s.lse_pass = 0;
   if (d.D == 128 && d.dtype == EA_BF16 && d.G % 4 == 0 && n >= 2048 && (int64_t)d.units() * (d.G / 4) <= 8) {
     // groups of four query heads at d = 128, calls of up to 8 (KV head, group) units: fragments in
     // registers, one wavefront per head, two workgroups of four wavefronts per CU.  Measured per
@@ -93,7 +94,8 @@ ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
   if (span < tile) span = tile;
   s.span = (int)span;
   s.nchunk = (int)((n + span - 1) / span);
-  s.pg = 32;
+  s.lse_pass = 1;
+  s.pg = kLseBlock;
   s.npart = (int)((n + s.pg - 1) / s.pg);
   return s;
 }

@@ -28,7 +28,8 @@ hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t
 // one LT per query head (used when a head has too many partials to reduce inside pass B)
 hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
                            const float* vnorm, const void* part, int npart, void* lse, float* scores,
-                           uint32_t* hist0, hipStream_t st, const float* wnorm = nullptr);
+                           uint32_t* hist0, hipStream_t st, const float* wnorm = nullptr, int lse_pass = 0);
+// lse_pass: the partials do not exist yet; take them from the (fp32) logits, one per kLseBlock keys
 // wnorm[i] = sqrt(max(2 d logits[i], 0)) for i < count
 hipError_t launch_wnorm(const void* logits, int logits_f64, size_t count, int D, float* wnorm, hipStream_t st);
 

@@ -1,9 +1,10 @@
 // Scoring kernels: Eq. 7 (expected unnormalised attention, as a logit), Eq. 8 (softmax over
 // all cached keys) and Eq. 9 with ||v|| and the GQA group mean.
 //
-//   pass A  k_score_mfma / k_score_f32 : stream K and V once; per key the G logits
-//           l_g = mu_g.k/sqrt(d) + k^T Sigma_g k/(2d) and ||v||; per workgroup an online
-//           (max, sum exp) pair per query head.
+//   pass A  k_score_mfma / k_score_hw / k_score_f32 : stream K and V once; per key the G logits
+//           l_g = mu_g.k/sqrt(d) + k^T Sigma_g k/(2d) and ||v||.
+//           (max, sum exp) per query head and fixed block of keys: k_score_hw and k_score_f32 keep
+//           them on the way, for k_score_mfma k_lse_part takes them from the stored logits.
 //   pass B  k_finalize : combine the pairs into log-sum-exp per head, then
 //           score = (mean_g exp(l_g - lse_g) + eps) * ||v||.
 #include "ea_score_mfma.h"
@@ -200,6 +201,42 @@ __device__ __forceinline__ LT wave_lse(const typename LT2<LT>::type* __restrict_
   return m + ea_log(s);
 }
 
+// (max, sum exp) of one block of kLseBlock keys of one query head, from the logits pass A stored:
+// the LDS-fragment kernels leave the softmax to this pass, so the partial of a block is the same
+// number on every run whichever waves scored its keys (fixed reduction tree), and the score
+// kernel's inner loop carries no exponentials or cross-lane reductions.  The logits were written
+// a moment ago and are read from the caches.
+__global__ __launch_bounds__(256) void k_lse_part(const float* __restrict__ logits, long long n, int npart,
+                                                  float2* __restrict__ part) {
+  constexpr int PER = kLseBlock / 256;
+  __shared__ float s_red[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int head = blockIdx.x / npart, j = blockIdx.x - head * npart;
+  const float* lp = logits + (size_t)head * n;
+  const long long base = (long long)j * kLseBlock;
+  float x[PER];
+#pragma unroll
+  for (int it = 0; it < PER; ++it) {          // no load under a condition: indices past the end are clamped
+    const long long i = base + it * 256 + tid;
+    const float v = lp[min(i, n - 1)];
+    x[it] = i < n ? v : -INFINITY;
+  }
+  float m = x[0];
+#pragma unroll
+  for (int it = 1; it < PER; ++it) m = fmaxf(m, x[it]);
+  for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  if (lane == 0) s_red[0][wave] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(s_red[0][0], s_red[0][1]), fmaxf(s_red[0][2], s_red[0][3]));   // a block holds a key: finite
+  float s = 0.f;
+#pragma unroll
+  for (int it = 0; it < PER; ++it) s += expf(x[it] - m);
+  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+  if (lane == 0) s_red[1][wave] = s;
+  __syncthreads();
+  if (tid == 0) part[(size_t)head * npart + j] = make_float2(m, (s_red[1][0] + s_red[1][1]) + (s_red[1][2] + s_red[1][3]));
+}
+
 // Heads with very many partials: one workgroup per query head reduces them once, ahead of
 // pass B (otherwise every workgroup of pass B would walk the whole list).
 template <typename LT>
@@ -323,7 +360,7 @@ constexpr int kLseInlineMax = 1024;   // more partials per head than this: reduc
 
 hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
                            const float* vnorm, const void* part, int npart, void* lse, float* scores,
-                           uint32_t* hist0, hipStream_t st, const float* wnorm) {
+                           uint32_t* hist0, hipStream_t st, const float* wnorm, int lse_pass) {
   // 1024 keys per workgroup; four rounds of them (fewer histogram flushes) once that still leaves
   // a few thousand workgroups: the pass is bound by memory latency and wants the chip full
   const int rounds = (n + 1023) / 1024 * d.units() >= 4096 ? 4 : 1;
@@ -336,6 +373,8 @@ hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int log
                                              pre ? (const double*)lse : nullptr, d.G, npart, n, d.eps,
                                              d.units(), rounds, scores, hist0, wnorm);
   } else {
+    if (lse_pass)
+      k_lse_part<<<(unsigned)((size_t)d.qheads() * npart), 256, 0, st>>>((const float*)logits, n, npart, (float2*)part);
     if (pre) k_lse<float><<<d.qheads(), 256, 0, st>>>((const float2*)part, npart, (float*)lse);
     k_finalize<float><<<grid, 256, 0, st>>>((const float*)logits, vnorm, (const float2*)part,
                                             pre ? (const float*)lse : nullptr, d.G, npart, n, d.eps,

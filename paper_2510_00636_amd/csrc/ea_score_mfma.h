@@ -30,9 +30,9 @@ struct ScoreArgs {
   const float* post;
   float* logits;
   float* vnorm;
-  float2* part;
+  float2* part;           // register-fragment kernel only: its (max, sum exp) partials
   int G, passes, nchunk, units, nfrag;     // nchunk: workgroups per (unit, pass)
-  int npart;              // (max, sum exp) partials per query head: partial j covers keys [pg*j, pg*j + pg)
+  int npart;              // that kernel: partials per query head, partial j covers keys [pg*j, pg*j + pg)
   int tpt;                // register-fragment kernel: tiles per ticket (pg = 32 * tpt); else unused
   uint32_t* tickets;      // tickets + unit * ticket_stride + pass * kTicketWays + way: tile counters, zero at launch
   int ticket_stride;
@@ -285,9 +285,9 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   // Results of a tile are stored one iteration later, right after the staging of the next
   // tile: global stores share the in-order counter of the loads, and stores issued while
   // loads are pending make every later wait for a load also wait for the store.
-  float lg_prev[GH], mt_prev[GH], st_prev[GH], vsq_prev = 0.f;
+  float lg_prev[GH], vsq_prev = 0.f;
 #pragma unroll
-  for (int g = 0; g < GH; ++g) { lg_prev[g] = 0.f; mt_prev[g] = 0.f; st_prev[g] = 0.f; }
+  for (int g = 0; g < GH; ++g) lg_prev[g] = 0.f;
   long long key_prev = 0;
   bool have_prev = false;
   auto store_prev = [&]() {
@@ -297,14 +297,6 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 #pragma unroll
       for (int g = 0; g < GH; ++g)
         if (g0 + g < a.G) a.logits[((size_t)unit * a.G + g0 + g) * a.n + key] = lg_prev[g];
-    }
-    // the tile's (max, sum exp) goes to the slot of its key block: whichever wave scored the
-    // tile, the finalize pass finds the same numbers in the same places
-    if (lane == 0) {
-#pragma unroll
-      for (int g = 0; g < GH; ++g)
-        if (g0 + g < a.G)
-          a.part[((size_t)unit * a.G + g0 + g) * a.npart + (key_prev >> 5)] = make_float2(mt_prev[g], st_prev[g]);
     }
     if (do_v) {
       const long long row = b0 + lch * RPL + lrow;
@@ -448,16 +440,11 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
         __builtin_amdgcn_sched_barrier(0);
       });
     }
-    const bool valid = tile_base(key0) + r >= key0 && tile_base(key0) + r < a.n;
+    // The softmax over keys (Eq. 8) is not this kernel's business: the (max, sum exp) partials are
+    // taken from the stored logits per fixed block of keys by a pass of their own (k_lse_part), so
+    // they do not depend on which wave scored which tile.
 #pragma unroll
-    for (int g = 0; g < GH; ++g) {
-      float lg = partial[g] * pq[g] + lin[g];
-      lg = sum_halves(lg);
-      lg_prev[g] = lg;
-      const float mt = max_lanes32(valid ? lg : -INFINITY);      // a tile always holds a valid key
-      mt_prev[g] = mt;
-      st_prev[g] = sum_lanes32(valid ? __expf(lg - mt) : 0.f);
-    }
+    for (int g = 0; g < GH; ++g) lg_prev[g] = sum_halves(partial[g] * pq[g] + lin[g]);
     vsq_prev = vsq;
     key_prev = key0;
     have_prev = true;
