@@ -129,7 +129,7 @@ def score_flops(ea, p_one, n, d, G):
     steps per tile of 32 keys and pass (triangular Sigma tiling plus the extra tile); the dense count
     is G (2 d^2 + 2 d) of Eq. 7."""
     NF = (d // 32) * (d // 32 + 1)
-    gh = {64: min(G, 8), 128: 4 if G % 4 == 0 else min(G, 5), 256: 1}[d]
+    gh = {64: min(G, 8), 128: 4 if G % 4 == 0 else min(G, 5), 256: min(G, 2)}[d]
     passes = -(-G // gh)
     nfrag = gh * NF + 2 * (d // 16)
     return passes * nfrag * 1024.0, G * (2.0 * d * d + 2 * d)

@@ -85,6 +85,14 @@ ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
     if (inst[i] >= need) s.GH = inst[i];
   s.nfrag = s.GH * NF + 2 * NKS;
   s.lds_bytes = (size_t)s.nfrag * 1024 + stage + slack;
+  if (d.D == 256 && d.G >= 2) {
+    // two query heads per pass: their triangular fragments in LDS (144 KiB), the extra tile's in
+    // registers, K staged through 4 KiB per wave: exactly the 160 KiB a workgroup may have
+    s.GH = 2;
+    s.passes = (d.G + 1) / 2;
+    s.nfrag = 2 * NF + 2 * NKS;
+    s.lds_bytes = (size_t)2 * NF * 1024 + (size_t)s.NW * 4096;
+  }
   const int tile = s.NW * 32;
   int64_t wgs = num_cu / d.units();
   if (wgs < 1) wgs = 1;

@@ -165,14 +165,21 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   constexpr int CPR = D / 8;            // 16-byte chunks per row
   constexpr int RPL = 64 / CPR;         // rows per wave-wide load
   constexpr int NL = 32 / RPL;          // wave-wide loads per 32-key tile
-  constexpr int NKH = NKS / 2;          // k-steps staged per phase
-  constexpr int RP = CPR / 2;           // staged chunks per row and phase
+  // Two query heads at d = 256: their triangular fragments fill 144 of the 160 KiB of LDS, so the
+  // extra tile's fragments live in registers (one wave per SIMD has 512 of them) and K is staged
+  // in four phases through a 4 KiB slab per wave.  Both heads then share one pass over K: every
+  // key is loaded, converted and staged once, and the extra tile is computed once for both.
+  constexpr bool XR = D == 256 && GH == 2;
+  constexpr int NPH = XR ? 4 : 2;       // staging phases per tile
+  constexpr int NLF = XR ? GH * NF : NFRAG;   // fragments held in LDS
+  constexpr int NKH = NKS / NPH;        // k-steps staged per phase
+  constexpr int RP = CPR / NPH;         // staged chunks per row and phase
   constexpr int RPS = 16 / RP;          // staged rows per 256 bytes (one sweep of the LDS banks)
   extern __shared__ u32x4 smem[];
   const half8* fr = reinterpret_cast<const half8*>(smem);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: lives in an SGPR
-  u32x4* stg = smem + NFRAG * 64 + wave * (16 * CPR);
+  u32x4* stg = smem + NLF * 64 + wave * (32 * RP);
 
   // Workgroups are dealt to the chip's 8 dies round-robin by index; the transposition below
   // gives every unit workgroups on all of them.  Together with the tile tickets further down it
@@ -209,15 +216,19 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   };
   const int t_cur_raw = grab();
   int t_nxt_raw = grab();
-  constexpr int NFIT = (NFRAG + NW - 1) / NW;
+  constexpr int NFIT = XR ? 1 : (NFRAG + NW - 1) / NW;
   u32x4 ftmp[NFIT];
-  {
-    const u32x4* src = a.frags + ((size_t)unit * a.passes + pass) * NFRAG * 64;
+  half8 xf[XR ? 2 * NKS : 1];            // XR: the extra tile's fragments
+  const u32x4* fsrc = a.frags + ((size_t)unit * a.passes + pass) * NFRAG * 64;
+  if constexpr (!XR) {
 #pragma unroll
     for (int it = 0; it < NFIT; ++it) {
       const int i = tid + it * NW * 64;
-      ftmp[it] = i < NFRAG * 64 ? src[i] : u32x4{0u, 0u, 0u, 0u};
+      ftmp[it] = i < NFRAG * 64 ? fsrc[i] : u32x4{0u, 0u, 0u, 0u};
     }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2 * NKS; ++i) xf[i] = __builtin_bit_cast(half8, fsrc[(GH * NF + i) * 64 + lane]);
   }
   float pq[GH], pm[GH];
 #pragma unroll
@@ -246,7 +257,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   // 14 % on the finalize pass.  At d = 256 a KV head's query heads take one pass over K each
   // (their fragments do not fit in LDS together); the passes run side by side, and there K is
   // loaded with the default policy so that the second reader finds it in a cache (5 %).
-  constexpr bool kNtK = D <= 128;
+  constexpr bool kNtK = D <= 128 || XR;
   u32x4 kraw[NL], vraw[NL];
   auto tile_base = [&](long long k0) -> long long {          // first row actually loaded
     return (!CLAMP && k0 + 32 > a.n) ? a.n - 32 : k0;
@@ -275,10 +286,22 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     }
   }
 
+  if constexpr (!XR) {
 #pragma unroll
-  for (int it = 0; it < NFIT; ++it) {
-    const int i = tid + it * NW * 64;
-    if (i < NFRAG * 64) smem[i] = ftmp[it];
+    for (int it = 0; it < NFIT; ++it) {
+      const int i = tid + it * NW * 64;
+      if (i < NFRAG * 64) smem[i] = ftmp[it];
+    }
+  } else {
+    // 144 fragments through a few registers at a time (the prologue runs once per workgroup)
+    static_assert(!XR || NLF % (4 * NW) == 0, "fragment count");
+    for (int b = 0; b < NLF / NW; b += 4) {
+      u32x4 t[4];
+#pragma unroll
+      for (int it = 0; it < 4; ++it) t[it] = fsrc[tid + (b + it) * NW * 64];
+#pragma unroll
+      for (int it = 0; it < 4; ++it) smem[tid + (b + it) * NW * 64] = t[it];
+    }
   }
   __syncthreads();
 
@@ -310,7 +333,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     //      of every lane's k-steps for all 32 rows (half-size buffer, all lanes busy).
     half8 Kh[NKS];
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
+    for (int hf = 0; hf < NPH; ++hf) {
       if (((lch % NKS) / NKH) == hf) {
         const int sc = (lch / NKS) * NKH + (lch % NKH);
 #pragma unroll
@@ -362,9 +385,13 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
       constexpr int NX = 2 * NKS, NS = NX + GH * NF, NT = GH * NJT, PD = GH >= 5 ? 3 : kFragPrefetch;
       half8 fb[PD + 1];
       floatx16 ex, accb[3];
+      // step f reads LDS fragment lfrag(f) into ring slot f % (PD + 1); with the extra tile in
+      // registers the LDS stream starts at step NX
+      constexpr int F0 = XR ? NX : 0;
+      auto lfrag = [](int f) constexpr { return XR ? f - NX : step_frag<GH, NF, NX>(f); };
       static_for<PD>([&](auto i_) {
         constexpr int i = decltype(i_)::value;
-        fb[i] = fr[step_frag<GH, NF, NX>(i) * 64 + lane];
+        fb[(F0 + i) % (PD + 1)] = fr[lfrag(F0 + i) * 64 + lane];
       });
       __builtin_amdgcn_sched_barrier(0);
       // FMAs 4q .. 4q+3 of the dot product of tile tt
@@ -383,9 +410,11 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
       static_for<NS + 6>([&](auto f_) {
         constexpr int f = decltype(f_)::value;
         if constexpr (f < NS) {
-          if constexpr (f + PD < NS)
-            fb[(f + PD) % (PD + 1)] = fr[step_frag<GH, NF, NX>(f + PD) * 64 + lane];
-          const half8 A = fb[f % (PD + 1)];
+          if constexpr (f + PD < NS && f >= F0)
+            fb[(f + PD) % (PD + 1)] = fr[lfrag(f + PD) * 64 + lane];
+          half8 A;
+          if constexpr (XR && f < NX) A = xf[f];
+          else A = fb[f % (PD + 1)];
           constexpr floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
           if constexpr (f < NKS) {
             ex = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, Kh[f], f == 0 ? zero : ex, 0, 0, 0);

@@ -118,6 +118,22 @@ def test_score_group_shapes(hq, hkv):
         P.check_scores(got, ref, 2e-3)
 
 
+@pytest.mark.parametrize("hq,hkv,n", [(2, 1, 4100), (3, 1, 2077), (8, 2, 1300), (2, 1, 20)])
+def test_score_d256_two_heads_per_pass(hq, hkv, n):
+    """Head dimension 256 with both query heads of a pair in one pass over K (extra tile's
+    fragments in registers): a full pair, an odd group (last pass half empty), two passes of pairs,
+    and a head shorter than one tile."""
+    cfg = CONFIGS["c4"].with_(batch=1, n_q_heads=hq, n_kv_heads=hkv)
+    lay = make_layer(cfg, n=max(n, 40), window=16)
+    lay = dict(lay, n=n, k=np.ascontiguousarray(lay["k"][:, :, :n]), v=np.ascontiguousarray(lay["v"][:, :, :n]))
+    rmu, rsg = _oracle_stats(cfg, lay)
+    mu32, sg32 = rmu.astype(np.float32), rsg.astype(np.float32)
+    for eps in (0.02, 0.0):
+        got = P.run_score(cfg, lay, mu32, sg32, eps, n_cap=n + 5)
+        ref = O.scores(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), sg32.astype(np.float64), eps)
+        P.check_scores(got, ref, 2e-3)
+
+
 def test_score_zero_covariance_and_zero_mean():
     cfg = CONFIGS["c2"].with_(n_q_heads=4, n_kv_heads=1)
     lay = make_layer(cfg, n=600, window=8)
