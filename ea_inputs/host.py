@@ -130,3 +130,25 @@ def make_layer(cfg: CacheConfig, layer: int = 0, *, n: int = None, window: int =
                 q_win[b, hq] = _store(x, cfg.dtype)
     return dict(q_win=q_win, k=k, v=v, inv_freq=inv_freq, q_pos0=int(qpos[0]),
                 t_next=int(pos0 + n), n=n, window=w)
+
+
+def make_block_pools(k, v, block_size, seed, spare_blocks=3):
+    """Scatters contiguous caches k, v [B, Hkv, n, d] into block pools [num_blocks, Hkv, block_size, d]
+    through a seeded random block table [B, max_blocks] (every logical block gets a pool block of
+    its own; the pool holds `spare_blocks` blocks more than needed, filled with a marker pattern,
+    as are the unused rows of each sequence's last block).  Returns (k_pool, v_pool, table, num_blocks)."""
+    B, H, n, d = k.shape
+    mb = -(-n // block_size)
+    num_blocks = B * mb + spare_blocks
+    rng = np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFF, 0x9A6ED]))
+    table = rng.permutation(num_blocks)[:B * mb].reshape(B, mb).astype(np.int32)
+    marker = 0x7FC0 if k.dtype == np.uint16 else np.nan          # NaN in either storage type
+    pools = []
+    for t in (k, v):
+        pool = np.full((num_blocks, H, block_size, d), marker, dtype=t.dtype)
+        for b in range(B):
+            for j in range(mb):
+                rows = t[b, :, j * block_size:(j + 1) * block_size]
+                pool[table[b, j], :, :rows.shape[1]] = rows
+        pools.append(pool)
+    return pools[0], pools[1], table, num_blocks

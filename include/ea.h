@@ -28,8 +28,8 @@
  *     Query head g belongs to KV head g / (Hq/Hkv).
  *   - Channel pairing of the rotary embedding: rope_layout 0 pairs (c, c+d/2), 1 pairs
  *     (2c, 2c+1); pair c turns by position * inv_freq[c].
- *   - Domain: finite inputs; bf16 keys must satisfy |k| < 4096 (they are narrowed to fp16
- *     for the matrix cores, and their squares are formed in fp16 after a 2^-4 scaling);
+ *   - Domain: finite inputs; bf16 keys are narrowed to fp16 for the matrix cores, so
+ *     |k| <= 65504 (the squared keys of the diagonal correction saturate for |k| > 4096);
  *     1 <= n <= 2^26 rows per head.  Measurement and debugging calls (they block) are in
  *     ea_profile.h, not here.
  */
@@ -203,6 +203,37 @@ ea_status ea_compress_layer_unordered(const ea_params* p, const void* q_win, int
                                       void* v, int64_t n, int64_t n_cap, int64_t n_keep,
                                       float* scores_out, int32_t* idx_out, int32_t* perm_out, void* ws,
                                       size_t ws_bytes, void* stream);
+
+/* Paged caches (the block-table layout of paged-attention servers), for the cache of Listing 1
+ * when it does not live in one tensor per head: K and V are pools
+ *   k_pool, v_pool  [num_blocks, Hkv, block_size, d]   bf16
+ * and logical block j of sequence b (its rows j*block_size .. (j+1)*block_size - 1, for all of the
+ * sequence's KV heads) is pool block block_table[b, j].  The three calls below are ea_score,
+ * ea_compact (in place) and ea_compress_layer over such a cache: same arithmetic, same results for
+ * the same logical rows.  After a compaction the logical rows [0, n_keep) of every head are valid;
+ * the blocks from ceil(n_keep / block_size) on hold nothing the cache needs and may be returned to
+ * the pool by the caller (the library never writes the table).  Table entries outside
+ * [0, num_blocks) are clamped into the pool (wrong results, no access outside it).
+ * order_free != 0 selects the order-free compaction (see ea_compact_unordered); perm_out is only
+ * written then (nullable).  EA_ERR_UNSUPPORTED for fp32 caches and for block sizes that are not a
+ * power of two in [32, 65536]. */
+typedef struct {
+  const int32_t* block_table; /* DEVICE [B, max_blocks] int32                                */
+  int32_t block_size;         /* rows per block                                              */
+  int32_t max_blocks;         /* entries per sequence in block_table; max_blocks * block_size >= n */
+  int64_t num_blocks;         /* blocks in each pool                                         */
+} ea_paged;
+ea_status ea_score_paged(const ea_params* p, const void* k_pool, const void* v_pool, const ea_paged* pg,
+                         int64_t n, const float* mu, const float* sigma, float* scores, void* ws,
+                         size_t ws_bytes, void* stream);
+ea_status ea_compact_paged(const ea_params* p, void* k_pool, void* v_pool, const ea_paged* pg, int64_t n,
+                           const int32_t* idx, int64_t n_keep, int32_t order_free, int32_t* perm_out,
+                           void* ws, size_t ws_bytes, void* stream);
+ea_status ea_compress_layer_paged(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                                  const double* inv_freq, int64_t t_next, void* k_pool, void* v_pool,
+                                  const ea_paged* pg, int64_t n, int64_t n_keep, int32_t order_free,
+                                  float* scores_out, int32_t* idx_out, int32_t* perm_out, void* ws,
+                                  size_t ws_bytes, void* stream);
 
 /* Listing 1: int(n * (1 - ratio)) in IEEE double, truncated toward zero; -1 if ratio is
  * outside [0, 1] or n < 0.  Host only. */

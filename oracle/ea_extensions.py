@@ -10,6 +10,7 @@ cpu_baseline leg may import it; it shares nothing with the HIP library).
   compact_ragged         the gather of Listing 1 with a different kept count per head
   query_stats_hidden     Eq. 5 as printed: statistics of the hidden states, pushed through W_Q
   scores_wo              Eq. 9 as printed: ||W_o v|| instead of ||v||
+  paged_rows             block-table ("paged") cache layout: which pool row holds a logical row
   knorm / streaming / keydiff scores   the comparison scorers of Sec. 3.1 ("Baselines"), from the one
                          sentence the paper gives each, on the same select + compact back half
 
@@ -33,7 +34,8 @@ count is the minimum possible); adaptive selection vs a flat stable sort and its
 scores reduce to the per-head rule); hidden-state statistics vs the projected-query route of
 ea_oracle.query_stats (Eq. 5's linearity); ||W_o v|| vs numpy.linalg.norm of the explicit product
 and the W_o = I reduction to ea_oracle.scores; the scorers vs their one-line definitions on
-hand-made keys.
+hand-made keys; the paged layout vs a pool written out by hand and vs the input generator's
+separately coded scatter.
 """
 import math
 
@@ -182,3 +184,17 @@ def keydiff_scores(k):
     with np.errstate(invalid="ignore", divide="ignore"):
         cos = np.where(an > 0, (u * a).sum(axis=-1, keepdims=True) / an, 0.0)
     return 1.0 - cos[..., 0]
+
+
+# ------------------------------------------------------------------ paged cache layout (f3)
+def paged_rows(pool, table, n):
+    """Logical view of a paged cache: pool [num_blocks, Hkv, block_size, d], table [B, max_blocks]
+    (pool block of every logical block of every sequence) -> [B, Hkv, n, d], where logical row i of
+    sequence b and head h is pool[table[b, i // block_size], h, i % block_size]."""
+    pool, table = np.asarray(pool), np.asarray(table)
+    B, bs = table.shape[0], pool.shape[2]
+    out = np.empty((B, pool.shape[1], n, pool.shape[3]), pool.dtype)
+    for b in range(B):
+        for i in range(n):
+            out[b, :, i] = pool[table[b, i // bs], :, i % bs]
+    return out

@@ -24,6 +24,11 @@ class EaParams(ctypes.Structure):
                 ("horizon_T", ctypes.c_int32), ("epsilon", ctypes.c_float)]
 
 
+class EaPaged(ctypes.Structure):
+    _fields_ = [("block_table", ctypes.c_void_p), ("block_size", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32), ("num_blocks", ctypes.c_int64)]
+
+
 def lib_path():
     """In-tree libea.so; the environment variable EA_LIBRARY names another build of it."""
     return os.environ.get("EA_LIBRARY") or os.path.join(_HERE, "libea.so")
@@ -73,6 +78,14 @@ def load_library():
     lib.ea_compact_unordered.argtypes = [P, VP, VP, I64, I64, VP, I64, VP, VP]
     lib.ea_compress_layer_unordered.restype = ctypes.c_int
     lib.ea_compress_layer_unordered.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, VP, VP, VP, SZ, VP]
+    PG = ctypes.POINTER(EaPaged)
+    lib.ea_score_paged.restype = ctypes.c_int
+    lib.ea_score_paged.argtypes = [P, VP, VP, PG, I64, VP, VP, VP, VP, SZ, VP]
+    lib.ea_compact_paged.restype = ctypes.c_int
+    lib.ea_compact_paged.argtypes = [P, VP, VP, PG, I64, VP, I64, ctypes.c_int32, VP, VP, SZ, VP]
+    lib.ea_compress_layer_paged.restype = ctypes.c_int
+    lib.ea_compress_layer_paged.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, PG, I64, I64, ctypes.c_int32,
+                                            VP, VP, VP, VP, SZ, VP]
     lib.ea_compress_layer_timed.restype = ctypes.c_int
     lib.ea_compress_layer_timed.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, SZ, VP,
                                             ctypes.POINTER(ctypes.c_float)]
@@ -226,6 +239,32 @@ def compress_layer_unordered(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n
                                                       _ptr(scores_out), _ptr(idx_out), _ptr(perm_out),
                                                       _ptr(ws), _nbytes(ws), _stream(stream)),
            "ea_compress_layer_unordered")
+
+
+def make_paged(block_table, block_size, num_blocks):
+    """ea_paged for a block table tensor [B, max_blocks] int32 on the device."""
+    return EaPaged(block_table.data_ptr(), int(block_size), int(block_table.shape[-1]), int(num_blocks))
+
+
+def score_paged(p, k_pool, v_pool, pg, n, mu, sigma, scores, ws, stream=None):
+    _check(load_library().ea_score_paged(ctypes.byref(p), _ptr(k_pool), _ptr(v_pool), ctypes.byref(pg), int(n),
+                                         _ptr(mu), _ptr(sigma), _ptr(scores), _ptr(ws), _nbytes(ws),
+                                         _stream(stream)), "ea_score_paged")
+
+
+def compact_paged(p, k_pool, v_pool, pg, n, idx, n_keep_, order_free, perm_out, ws, stream=None):
+    _check(load_library().ea_compact_paged(ctypes.byref(p), _ptr(k_pool), _ptr(v_pool), ctypes.byref(pg), int(n),
+                                           _ptr(idx), int(n_keep_), int(order_free), _ptr(perm_out), _ptr(ws),
+                                           _nbytes(ws), _stream(stream)), "ea_compact_paged")
+
+
+def compress_layer_paged(p, q_win, window, q_pos0, inv_freq, t_next, k_pool, v_pool, pg, n, n_keep_, order_free,
+                         scores_out, idx_out, perm_out, ws, stream=None):
+    _check(load_library().ea_compress_layer_paged(ctypes.byref(p), _ptr(q_win), int(window), int(q_pos0),
+                                                  _ptr(inv_freq), int(t_next), _ptr(k_pool), _ptr(v_pool),
+                                                  ctypes.byref(pg), int(n), int(n_keep_), int(order_free),
+                                                  _ptr(scores_out), _ptr(idx_out), _ptr(perm_out), _ptr(ws),
+                                                  _nbytes(ws), _stream(stream)), "ea_compress_layer_paged")
 
 
 N_STAGES = 6

@@ -57,21 +57,22 @@ static ea_status run_stats(const Dims& d, const void* q_win, int64_t window, int
 static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                            const float* mu, const float* sigma, float* scores, uint32_t* hist0,
                            bool hist_zeroed, char* ws, const WsLayout& L, hipStream_t st,
-                           hipEvent_t* ev = nullptr, const float* wnorm = nullptr, float* wnorm_out = nullptr) {
+                           hipEvent_t* ev = nullptr, const float* wnorm = nullptr, float* wnorm_out = nullptr,
+                           const PageMap* pm = nullptr) {
   // wnorm: Eq. 9 with per-query-head norms ||W_o v||.  wnorm_out: stop after pass A and turn its
   // quadratic forms into such norms (the caller passed the values as keys, mu = 0, Sigma = M_g).
   float* vnorm = (float*)(ws + L.vnorm);
   uint32_t* hist = (uint32_t*)(ws + L.hist);
   if (d.dtype == EA_BF16 && !hist_zeroed) EA_TRY(launch_zero(hist, (size_t)d.units() * 3 * kSelBins, st));
   if (d.dtype == EA_BF16) {
-    ScorePlan sp = make_score_plan(d, n, device_num_cu());
+    ScorePlan sp = make_score_plan(d, n, device_num_cu(), pm != nullptr);
     uint4* frags = (uint4*)(ws + L.frags);
     float* post = (float*)(ws + L.post);
     EA_TRY(launch_prep_frags(d, sp, mu, sigma, frags, post, st));
     if (ev) EA_TRY(hipEventRecord(ev[0], st));
     EA_TRY(launch_score_mfma(d, sp, k, v, n, n_cap, frags, post, (float*)(ws + L.logits), vnorm,
                              (float2*)(ws + L.part), hist + 2 * kSelBins + kTicketSlot, 3 * kSelBins,
-                             st));
+                             st, pm));
     if (ev) EA_TRY(hipEventRecord(ev[1], st));
     if (wnorm_out) return launch_wnorm(ws + L.logits, 0, (size_t)d.qheads() * n, d.D, wnorm_out, st) == hipSuccess
                               ? EA_OK : EA_ERR_DEVICE;
@@ -300,12 +301,32 @@ ea_status ea_compact(const ea_params* p, const void* k, const void* v, int64_t n
   return EA_OK;
 }
 
+// ea_paged -> PageMap, validated on the host (the table's entries are device memory: the kernels
+// clamp them into the pool)
+static ea_status check_paged(const Dims& d, const ea_paged* pg, int64_t n, PageMap* pm) {
+  if (!pg || !pg->block_table || ((uintptr_t)pg->block_table & 3u)) return EA_ERR_INVALID_ARG;
+  const int64_t bs = pg->block_size;
+  if (bs < 32 || bs > 65536 || (bs & (bs - 1)) != 0) return EA_ERR_UNSUPPORTED;
+  if (pg->max_blocks < 1 || pg->num_blocks < 1 || pg->num_blocks > ((int64_t)1 << 31)) return EA_ERR_INVALID_ARG;
+  if ((int64_t)pg->max_blocks * bs < n) return EA_ERR_INVALID_ARG;
+  if (d.dtype != EA_BF16) return EA_ERR_UNSUPPORTED;
+  pm->table = pg->block_table;
+  pm->sh = 0;
+  while (((int64_t)1 << pm->sh) < bs) ++pm->sh;
+  pm->max_blocks = pg->max_blocks;
+  pm->hkv = d.Hkv;
+  pm->num_blocks = pg->num_blocks;
+  return EA_OK;
+}
+
 // unordered: the order-free compaction (perm_out then receives the source row of every position)
+// pm: the caches are block pools (n_cap is then not used)
 static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t window,
                                int64_t q_pos0, const double* inv_freq, int64_t t_next, void* k,
                                void* v, int64_t n, int64_t n_cap, int64_t n_keep, float* scores_out,
                                int32_t* idx_out, void* ws, size_t ws_bytes, void* stream,
-                               hipEvent_t* ev, bool unordered = false, int32_t* perm_out = nullptr) {
+                               hipEvent_t* ev, bool unordered = false, int32_t* perm_out = nullptr,
+                               const PageMap* pm = nullptr) {
   Dims d;
   ea_status s = check_params(p, &d);
   if (s != EA_OK) return s;
@@ -339,16 +360,17 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
   if (ev) EA_TRY(hipEventRecord(ev[1], st));
   if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores,
                      n_keep > 0 && !select_in_one_launch(n) ? hist : nullptr, true, w, L, st,
-                     ev ? ev + 2 : nullptr)) != EA_OK)
+                     ev ? ev + 2 : nullptr, nullptr, nullptr, pm)) != EA_OK)
     return s;
   if (ev) EA_TRY(hipEventRecord(ev[4], st));
   if (n_keep > 0)
     EA_TRY(launch_select(d, scores, n, n_keep, idx, hist, (uint32_t*)(w + L.blk), true, st));
   if (ev) EA_TRY(hipEventRecord(ev[5], st));
   if (n_keep > 0 && unordered)
-    EA_TRY(launch_compact_fill(d, k, v, n, n_cap, idx, n_keep, perm_out, st));
+    EA_TRY(launch_compact_fill(d, k, v, n, n_cap, idx, n_keep, perm_out, st, pm));
   else if (n_keep > 0)
-    EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k, v, flags, hist + 2 * kSelBins + kStatusSlot, st));
+    EA_TRY(launch_compact(d, k, v, n, n_cap, idx, n_keep, k, v, flags, hist + 2 * kSelBins + kStatusSlot, st,
+                          nullptr, 0, pm));
   if (ev) EA_TRY(hipEventRecord(ev[6], st));
   return EA_OK;
 }
@@ -457,6 +479,73 @@ ea_status ea_compress_layer_unordered(const ea_params* p, const void* q_win, int
                                       size_t ws_bytes, void* stream) {
   return compress_impl(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep,
                        scores_out, idx_out, ws, ws_bytes, stream, nullptr, true, perm_out);
+}
+
+ea_status ea_score_paged(const ea_params* p, const void* k_pool, const void* v_pool, const ea_paged* pg,
+                         int64_t n, const float* mu, const float* sigma, float* scores, void* ws,
+                         size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(k_pool) || !aligned16(v_pool) || !aligned16(mu) || !aligned16(sigma) || !aligned16(scores))
+    return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > kMaxN) return EA_ERR_INVALID_ARG;
+  PageMap pm;
+  if ((s = check_paged(d, pg, n, &pm)) != EA_OK) return s;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  return run_score(d, k_pool, v_pool, n, 0, mu, sigma, scores, nullptr, false, (char*)ws, L,
+                   (hipStream_t)stream, nullptr, nullptr, nullptr, &pm);
+}
+
+ea_status ea_compact_paged(const ea_params* p, void* k_pool, void* v_pool, const ea_paged* pg, int64_t n,
+                           const int32_t* idx, int64_t n_keep, int32_t order_free, int32_t* perm_out,
+                           void* ws, size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(k_pool) || !aligned16(v_pool) || k_pool == v_pool) return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > kMaxN || n_keep < 0 || n_keep > n) return EA_ERR_INVALID_ARG;
+  if (n_keep > 0 && (!aligned16(idx) || (perm_out && !aligned16(perm_out)))) return EA_ERR_INVALID_ARG;
+  PageMap pm;
+  if ((s = check_paged(d, pg, n, &pm)) != EA_OK) return s;
+  {
+    const size_t bytes = (size_t)pg->num_blocks * d.Hkv * pg->block_size * d.D * d.esize();
+    if (partly_overlap(k_pool, v_pool, bytes)) return EA_ERR_INVALID_ARG;
+  }
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  if (n_keep == 0) return EA_OK;
+  hipStream_t st = (hipStream_t)stream;
+  if (order_free) {
+    EA_TRY(launch_compact_fill(d, k_pool, v_pool, n, 0, idx, n_keep, perm_out, st, &pm));
+    return EA_OK;
+  }
+  uint32_t* flags = (uint32_t*)((char*)ws + L.flags);
+  uint32_t* status = (uint32_t*)((char*)ws + L.hist) + 2 * kSelBins + kStatusSlot;
+  EA_TRY(launch_zero(flags, flag_words(d, n_keep), st, status));
+  EA_TRY(launch_compact(d, k_pool, v_pool, n, 0, idx, n_keep, k_pool, v_pool, flags, status, st, nullptr, 0, &pm));
+  return EA_OK;
+}
+
+ea_status ea_compress_layer_paged(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                                  const double* inv_freq, int64_t t_next, void* k_pool, void* v_pool,
+                                  const ea_paged* pg, int64_t n, int64_t n_keep, int32_t order_free,
+                                  float* scores_out, int32_t* idx_out, int32_t* perm_out, void* ws,
+                                  size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (n < 1 || n > kMaxN) return EA_ERR_INVALID_ARG;
+  PageMap pm;
+  if ((s = check_paged(d, pg, n, &pm)) != EA_OK) return s;
+  if (aligned16(k_pool) && aligned16(v_pool) &&
+      partly_overlap(k_pool, v_pool, (size_t)pg->num_blocks * d.Hkv * pg->block_size * d.D * d.esize()))
+    return EA_ERR_INVALID_ARG;
+  // n_cap = n for the shared checks; the kernels do not use it with a page map
+  return compress_impl(p, q_win, window, q_pos0, inv_freq, t_next, k_pool, v_pool, n, n, n_keep, scores_out,
+                       idx_out, ws, ws_bytes, stream, nullptr, order_free != 0, order_free ? perm_out : nullptr,
+                       &pm);
 }
 
 ea_status ea_compress_layer_timed(const ea_params* p, const void* q_win, int64_t window,

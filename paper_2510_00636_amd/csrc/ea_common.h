@@ -40,6 +40,14 @@ struct ScorePlan {
   size_t lds_bytes;
 };
 
+// Paged caches: K and V are pools [num_blocks][Hkv][bs][d]; logical block j of sequence b is pool
+// block table[b * max_blocks + j]; bs = 1 << sh.  table == nullptr: contiguous tensors.
+struct PageMap {
+  const int32_t* table;
+  int sh, max_blocks, hkv;
+  long long num_blocks;
+};
+
 struct WsLayout {
   size_t tab, qproj, mu, sigma, frags, post, logits, vnorm, part, lse, scores, idx, base, hist, blk, flags, total;
 };
@@ -47,7 +55,8 @@ struct WsLayout {
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 ea_status check_params(const ea_params* p, Dims* d);
-ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu);
+// paged: the caches are block pools (the register-fragment kernel does not read those)
+ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu, int paged = 0);
 WsLayout make_ws_layout(const Dims& d, int64_t n, int64_t window);
 
 // Free words of unit 0's third radix histogram (its last digit has 1024 bins): (T, q) of the

@@ -34,6 +34,7 @@ struct CompactArgs {
   uint32_t* status;   // status word (bits kStatusCompactWait, kStatusBadIndex)
   const int32_t* lengths;   // nullable: kept rows of every unit (head-adaptive budgets); then n_keep is
   long long idx_stride;     // only the grid's upper bound, and a unit's list starts at unit * idx_stride
+  PageMap pm;               // PAGED instances: src / dst are block pools (in place)
 };
 
 // First x in [0, c) for which the monotone predicate pred(x) (false ... false true ... true)
@@ -67,7 +68,7 @@ __device__ int first_true(int c, int lane, Pred pred) {
 // "everything I wait for is already running" argument holds per counter, and the counters
 // (one per tensor, in separate cache lines) are not a serial bottleneck the way one global
 // counter is.
-template <int RB>
+template <int RB, bool PAGED>
 __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   constexpr int CPR = RB / 16;                 // 16-byte pieces per row
   constexpr int NLD = kCompactRows * CPR / 256;
@@ -92,8 +93,10 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   const int j0 = c * kCompactRows, j1 = min(j0 + kCompactRows, n_keep);
   if (j0 >= n_keep) return;           // ragged lists: this unit has fewer chunks than the grid allows for
   const int32_t* idx = a.idx + (size_t)unit * a.idx_stride;
-  const u32x4* src = a.src[tensor] + (size_t)unit * a.n_cap * CPR;
-  u32x4* dst = a.dst[tensor] + (size_t)unit * a.n_cap * CPR;
+  const u32x4* src = a.src[tensor] + (PAGED ? (size_t)0 : (size_t)unit * a.n_cap * CPR);
+  u32x4* dst = a.dst[tensor] + (PAGED ? (size_t)0 : (size_t)unit * a.n_cap * CPR);
+  // row of the tensor (or, paged, of the pool) that holds logical row `row` of this unit
+  auto where = [&](int row) -> size_t { return PAGED ? paged_row(a.pm, unit, row) : (size_t)row; };
   // Rows are strictly ascending with idx[j] >= j, so idx[j1-1] == j1-1 means nothing moves.  Only
   // the control wavefront looks this up; the movers request their rows at once (waiting for the
   // answer would put one more memory round trip in front of every chunk) and learn it, through
@@ -114,6 +117,7 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   }
 
   u32x4 buf[NLD];
+  size_t drow[PAGED ? NLD : 1];      // PAGED: pool rows of the destinations, looked up with the loads
   if (!control) {
     // First every index, then every row, none of them under a per-thread condition: a load
     // inside "if (row < j1)" is followed by a wait for everything in flight, which made the
@@ -127,7 +131,11 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
       const int col = (tid + 256 * i) % CPR;
       // a malformed index can never leave the tensor: clamp to [0, n)
       // rows are read once and written once: non-temporal hints on both (4 % on this kernel)
-      buf[i] = __builtin_nontemporal_load(&src[(size_t)min(max(srow[i], 0), a.n - 1) * CPR + col]);
+      buf[i] = __builtin_nontemporal_load(&src[where(min(max(srow[i], 0), a.n - 1)) * CPR + col]);
+    }
+    if constexpr (PAGED) {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) drow[i] = where(min(j0 + (tid + 256 * i) / CPR, j1 - 1));
     }
     if (a.inplace) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // rows are in registers
   } else if (a.inplace && !identity) {
@@ -177,7 +185,8 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int e = tid + 256 * i, row = e / CPR, col = e % CPR;
-      if (j0 + row < j1) __builtin_nontemporal_store(buf[i], &dst[(size_t)(j0 + row) * CPR + col]);
+      const size_t to = PAGED ? drow[i] : (size_t)(j0 + row);
+      if (j0 + row < j1) __builtin_nontemporal_store(buf[i], &dst[to * CPR + col]);
     }
   }
 }
@@ -198,9 +207,10 @@ struct FillArgs {
   int32_t* perm;      // nullable: [units][n_keep], source row now at each position
   long long n_cap;
   int n, n_keep, units, nch;
+  PageMap pm;         // PAGED instances: t[] are block pools
 };
 
-template <int RB>
+template <int RB, bool PAGED>
 __global__ __launch_bounds__(256) void k_compact_fill(FillArgs a) {
   constexpr int CPR = RB / 16;
   constexpr int NLD = kFillRows * CPR / 256;
@@ -235,23 +245,26 @@ __global__ __launch_bounds__(256) void k_compact_fill(FillArgs a) {
     if (perm && tensor == 0 && i0 + tid < m) perm[dst] = src;
   }
   __syncthreads();
-  u32x4* base = a.t[tensor] + (size_t)unit * a.n_cap * CPR;
+  u32x4* base = a.t[tensor] + (PAGED ? (size_t)0 : (size_t)unit * a.n_cap * CPR);
+  auto where = [&](int row) -> size_t { return PAGED ? paged_row(a.pm, unit, row) : (size_t)row; };
   u32x4 buf[NLD];
 #pragma unroll
   for (int q = 0; q < NLD; ++q) {
     const int e = tid + 256 * q;
-    buf[q] = __builtin_nontemporal_load(&base[(size_t)s_src[e / CPR] * CPR + e % CPR]);
+    buf[q] = __builtin_nontemporal_load(&base[where(s_src[e / CPR]) * CPR + e % CPR]);
   }
 #pragma unroll
   for (int q = 0; q < NLD; ++q) {
     const int e = tid + 256 * q, row = e / CPR;
-    if (i0 + row < m) __builtin_nontemporal_store(buf[q], &base[(size_t)s_dst[row] * CPR + e % CPR]);
+    if (i0 + row < m) __builtin_nontemporal_store(buf[q], &base[where(s_dst[row]) * CPR + e % CPR]);
   }
 }
 
 hipError_t launch_compact_fill(const Dims& d, void* k, void* v, int64_t n, int64_t n_cap,
-                               const int32_t* idx, int64_t n_keep, int32_t* perm, hipStream_t st) {
+                               const int32_t* idx, int64_t n_keep, int32_t* perm, hipStream_t st,
+                               const PageMap* pm) {
   FillArgs a;
+  a.pm = pm ? *pm : PageMap{nullptr, 0, 0, 1, 0};
   a.t[0] = (u32x4*)k;
   a.t[1] = (u32x4*)v;
   a.idx = idx;
@@ -264,21 +277,28 @@ hipError_t launch_compact_fill(const Dims& d, void* k, void* v, int64_t n, int64
   a.nch = (int)((most + kFillRows - 1) / kFillRows);
   if (a.nch < 1) a.nch = 1;
   const unsigned grid = 2u * a.units * a.nch;
+#define EA_FILL(RB)                                                   \
+  case RB:                                                             \
+    if (pm) k_compact_fill<RB, true><<<grid, 256, 0, st>>>(a);         \
+    else k_compact_fill<RB, false><<<grid, 256, 0, st>>>(a);           \
+    break
   switch (d.D * d.esize()) {
-    case 128: k_compact_fill<128><<<grid, 256, 0, st>>>(a); break;
-    case 256: k_compact_fill<256><<<grid, 256, 0, st>>>(a); break;
-    case 512: k_compact_fill<512><<<grid, 256, 0, st>>>(a); break;
-    case 1024: k_compact_fill<1024><<<grid, 256, 0, st>>>(a); break;
+    EA_FILL(128);
+    EA_FILL(256);
+    EA_FILL(512);
+    EA_FILL(1024);
     default: return hipErrorInvalidValue;
   }
+#undef EA_FILL
   return hipGetLastError();
 }
 
 hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                           const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
                           uint32_t* flags, uint32_t* status, hipStream_t st, const int32_t* lengths,
-                          int64_t idx_stride) {
+                          int64_t idx_stride, const PageMap* pm) {
   CompactArgs a;
+  a.pm = pm ? *pm : PageMap{nullptr, 0, 0, 1, 0};
   a.lengths = lengths;
   a.idx_stride = lengths ? idx_stride : n_keep;
   a.n = (int)n;
@@ -296,13 +316,19 @@ hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n
   a.inplace = (k_out == k && v_out == v) ? 1 : 0;
   const int rb = d.D * d.esize();
   const unsigned grid = 2u * a.units * a.nch;
+#define EA_COMPACT(RB)                                                \
+  case RB:                                                             \
+    if (pm) k_compact<RB, true><<<grid, 320, 0, st>>>(a);              \
+    else k_compact<RB, false><<<grid, 320, 0, st>>>(a);                \
+    break
   switch (rb) {
-    case 128: k_compact<128><<<grid, 320, 0, st>>>(a); break;
-    case 256: k_compact<256><<<grid, 320, 0, st>>>(a); break;
-    case 512: k_compact<512><<<grid, 320, 0, st>>>(a); break;
-    case 1024: k_compact<1024><<<grid, 320, 0, st>>>(a); break;
+    EA_COMPACT(128);
+    EA_COMPACT(256);
+    EA_COMPACT(512);
+    EA_COMPACT(1024);
     default: return hipErrorInvalidValue;
   }
+#undef EA_COMPACT
   return hipGetLastError();
 }
 

@@ -37,12 +37,12 @@ ea_status check_params(const ea_params* p, Dims* d) {
 
 // Largest number of query heads whose fragments fit the 160 KiB LDS next to the per-wave
 // staging buffers, and the template instance (GH) that covers ceil(G / passes) heads.
-ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu) {
+ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu, int paged) {
   ScorePlan s;
   s.hw = 0;
   s.tpt = 1;
   s.lse_pass = 0;
-  if (d.D == 128 && d.dtype == EA_BF16 && d.G % 4 == 0 && n >= 2048 && (int64_t)d.units() * (d.G / 4) <= 8) {
+  if (!paged && d.D == 128 && d.dtype == EA_BF16 && d.G % 4 == 0 && n >= 2048 && (int64_t)d.units() * (d.G / 4) <= 8) {
     // groups of four query heads at d = 128, calls of up to 8 (KV head, group) units: fragments in
     // registers, one wavefront per head, two workgroups of four wavefronts per CU.  Measured per
     // layer of 8 KV heads x 131072 keys: 128 us against 129 us for the LDS-fragment kernel and a

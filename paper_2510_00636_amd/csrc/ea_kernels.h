@@ -6,6 +6,15 @@
 
 namespace ea {
 
+// pool row of logical row `row` of unit (b, h); a table entry outside the pool is clamped into it,
+// so a malformed table can never send an access outside the allocation
+__device__ __forceinline__ size_t paged_row(const PageMap& m, int unit, int row) {
+  const int b = unit / m.hkv, h = unit - b * m.hkv;
+  long long blk = m.table[(size_t)b * m.max_blocks + (row >> m.sh)];
+  blk = blk < 0 ? 0 : (blk >= m.num_blocks ? m.num_blocks - 1 : blk);
+  return ((size_t)(blk * m.hkv + h) << m.sh) + (size_t)(row & ((1 << m.sh) - 1));
+}
+
 // ea_stats.hip
 hipError_t launch_rope_table(const Dims& d, const double* inv_freq, int64_t q_pos0, int64_t t_next,
                              int w, float2* tab, uint32_t* clear, size_t clear_words, hipStream_t st);
@@ -19,7 +28,7 @@ hipError_t launch_prep_frags(const Dims& d, const ScorePlan& sp, const float* mu
 hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
                              float* logits, float* vnorm, float2* part, uint32_t* tickets,
-                             int ticket_stride, hipStream_t st);
+                             int ticket_stride, hipStream_t st, const PageMap* pm = nullptr);
 hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                             const float* mu, const float* sigma, double* logits, float* vnorm,
                             double2* part, int* nchunk_out, hipStream_t st);
@@ -46,7 +55,8 @@ hipError_t launch_zero(uint32_t* p, size_t count, hipStream_t st, uint32_t* extr
 hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                           const int32_t* idx, int64_t n_keep, void* k_out, void* v_out,
                           uint32_t* flags, uint32_t* status, hipStream_t st,
-                          const int32_t* lengths = nullptr, int64_t idx_stride = 0);
+                          const int32_t* lengths = nullptr, int64_t idx_stride = 0, const PageMap* pm = nullptr);
+// pm != nullptr: k and v are block pools (in place only; n_cap unused)
 // lengths != nullptr: unit u keeps lengths[u] <= n_keep rows, listed from idx + u * idx_stride
 
 // ea_select.hip, head-adaptive budgets: +inf into scores[unit][idx[unit][j]], j < n_mark; then the
@@ -58,7 +68,8 @@ hipError_t launch_split_pooled(const int32_t* flat, int B, int H, int64_t n, int
 // order-free variant, in place: only the kept rows at or beyond n_keep move, into the evicted
 // positions below it; perm (nullable) [units][n_keep] receives the source row of every position
 hipError_t launch_compact_fill(const Dims& d, void* k, void* v, int64_t n, int64_t n_cap,
-                               const int32_t* idx, int64_t n_keep, int32_t* perm, hipStream_t st);
+                               const int32_t* idx, int64_t n_keep, int32_t* perm, hipStream_t st,
+                               const PageMap* pm = nullptr);
 
 // ea_frontend.hip: q [B, Hq, w, d] fp32 = W_Q [Hq, d, dm] applied to hidden [B, w, dm] (dtype of d)
 hipError_t launch_project(const Dims& d, const void* hidden, const void* wq, int w, int dm, float* q,

@@ -14,8 +14,9 @@ namespace ea {
 hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
                              float* logits, float* vnorm, float2* part, uint32_t* tickets,
-                             int ticket_stride, hipStream_t st) {
+                             int ticket_stride, hipStream_t st, const PageMap* pm) {
   ScoreArgs a;
+  a.pm = pm ? *pm : PageMap{nullptr, 0, 0, 1, 0};
   a.k = (const u32x4*)k;
   a.v = (const u32x4*)v;
   a.n = n;

@@ -6,7 +6,7 @@ namespace ea {
 hipError_t launch_score_mfma_d128(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st) {
 #define EA_CASE(GG, WW)                 \
   if (sp.GH == GG && sp.NW == WW)     \
-  return a.n < 32 ? launch_one<128, GG, WW, true>(a, sp, st) : launch_one<128, GG, WW, false>(a, sp, st)
+  return (a.n < 32 || a.pm.table) ? launch_one<128, GG, WW, true>(a, sp, st) : launch_one<128, GG, WW, false>(a, sp, st)
   EA_CASE(1, kNW128);
   EA_CASE(2, kNW128);
   EA_CASE(3, kNW128);

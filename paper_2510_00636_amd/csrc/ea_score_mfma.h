@@ -36,6 +36,7 @@ struct ScoreArgs {
   int tpt;                // register-fragment kernel: tiles per ticket (pg = 32 * tpt); else unused
   uint32_t* tickets;      // tickets + unit * ticket_stride + pass * kTicketWays + way: tile counters, zero at launch
   int ticket_stride;
+  PageMap pm;             // pm.table != nullptr: k and v are block pools (CLAMP instances only)
 };
 
 __device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
@@ -156,8 +157,10 @@ constexpr int load_slot(int i) { return NX + (i * (NS - NX)) / (2 * NL); }
 //
 // Ragged tail: the last tile of a head is moved back to start at n - 32, so it overlaps its
 // predecessor instead of running past the tensor; the keys it shares with the predecessor are
-// recomputed and masked out of the stores and of the softmax sums.  Heads shorter than one tile
-// (n < 32) use the CLAMP instance, which clamps every row index instead.
+// recomputed and masked out of the stores.  The CLAMP instance clamps every row index to n - 1
+// instead (per-lane row offsets, a few more vector instructions per tile): it serves heads
+// shorter than one tile (n < 32) and paged caches, where a tile must not leave its block (tiles
+// then start at multiples of 32 and the block size is a multiple of 32).
 template <int D, int GH, int NW, bool CLAMP>
 __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   constexpr int NKS = D / 16, NJT = D / 32, NF = NJT * (NJT + 1);
@@ -249,6 +252,17 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   auto tile_key = [&](int ticket) -> long long { return (long long)(ntiles - 1 - ticket) * 32; };
   const u32x4* kbase = a.k + (size_t)unit * a.n_cap * CPR;
   const u32x4* vbase = a.v + (size_t)unit * a.n_cap * CPR;
+  // CLAMP: row offset (in 16-byte pieces) of this lane's piece of wave-wide load j of the tile at
+  // key0, rows past the end of the head clamped to its last row; first row of the tile inside
+  // the tensor or, for paged caches, inside the pool (a wave-uniform table lookup)
+  auto lane_off = [&](long long k0, int j) -> int {
+    const int lim = (int)min((long long)31, a.n - 1 - k0);
+    return min(j * RPL + lrow, lim) * CPR + lch;
+  };
+  auto tile_row0 = [&](long long k0) -> size_t {
+    if (a.pm.table) return paged_row(a.pm, unit, (int)k0);
+    return (size_t)unit * a.n_cap + k0;
+  };
 
   // One 32-key tile = NL wave-wide 16-byte loads per tensor, addressed as (uniform tile base)
   // + lane*16 + j*1024 so that the address arithmetic stays on the scalar unit.  K and V are
@@ -277,11 +291,11 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
         for (int j = 0; j < NL; ++j) vraw[j] = __builtin_nontemporal_load(&vp[j * 64 + lane]);
       }
     } else {
+      const size_t r0 = tile_row0(key0) * CPR;
 #pragma unroll
       for (int j = 0; j < NL; ++j) {
-        const long long row = min(key0 + j * RPL + lrow, a.n - 1);
-        kraw[j] = kbase[row * CPR + lch];
-        if (do_v) vraw[j] = vbase[row * CPR + lch];
+        kraw[j] = a.k[r0 + lane_off(key0, j)];
+        if (do_v) vraw[j] = a.v[r0 + lane_off(key0, j)];
       }
     }
   }
@@ -364,6 +378,14 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     const u32x4* vp_n = (has_next && do_v) ? vbase + tile_base(nkey0) * CPR : vbase;
     const int kl = has_next ? lane : 0, vl = (has_next && do_v) ? lane : 0;
     const int kj = has_next ? 64 : 0, vj = (has_next && do_v) ? 64 : 0;
+    int noff[CLAMP ? NL : 1];           // CLAMP: per-lane piece offsets of the next tile's loads
+    if constexpr (CLAMP) {
+      const size_t r0 = has_next ? tile_row0(nkey0) * CPR : (size_t)0;
+      kp_n = has_next ? a.k + r0 : kbase;
+      vp_n = (has_next && do_v) ? a.v + r0 : vbase;
+#pragma unroll
+      for (int j = 0; j < NL; ++j) noff[j] = has_next ? lane_off(nkey0, j) : 0;
+    }
 
     // ---- matrix-core phase: NS = 2*NKS + GH*NF steps, one LDS fragment and one MFMA each.
     //   steps [0, NKS)       extra tile, rows g / GH+g = fp16 head / tail of mu, times k
@@ -459,8 +481,13 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
         static_for<2 * NL>([&](auto i_) {
           constexpr int i = decltype(i_)::value;
           if constexpr (f < NS && load_slot<NX, NS, NL>(i) == f) {
-            if constexpr (i < NL) kraw[i] = kNtK ? __builtin_nontemporal_load(&kp_n[i * kj + kl]) : kp_n[i * kj + kl];
-            else vraw[i - NL] = __builtin_nontemporal_load(&vp_n[(i - NL) * vj + vl]);
+            if constexpr (CLAMP) {
+              if constexpr (i < NL) kraw[i] = kNtK ? __builtin_nontemporal_load(&kp_n[noff[i]]) : kp_n[noff[i]];
+              else vraw[i - NL] = __builtin_nontemporal_load(&vp_n[do_v ? noff[i - NL] : 0]);
+            } else {
+              if constexpr (i < NL) kraw[i] = kNtK ? __builtin_nontemporal_load(&kp_n[i * kj + kl]) : kp_n[i * kj + kl];
+              else vraw[i - NL] = __builtin_nontemporal_load(&vp_n[(i - NL) * vj + vl]);
+            }
           }
         });
         // Nothing may move across a step: the program order written above -- fragment read PD

@@ -120,3 +120,23 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "one GPU" in r.stderr
     assert r.stdout.strip() == ""
+
+
+def test_paged_arguments_are_checked_on_the_host(lib):
+    """Block sizes that are not a power of two in [32, 65536], tables too short for n, null tables
+    and fp32 caches are turned away before any launch (no GPU needed: the checks come first)."""
+    import ctypes
+    from paper_2510_00636_amd.binding import EaPaged, make_params, EA_BF16, EA_F32
+    p = make_params(1, 4, 2, 128, EA_BF16)
+    ws_bytes = lib.ea_workspace_bytes(ctypes.byref(p), 4096, 1)
+    fake = ctypes.c_void_p(0x10000)          # never dereferenced: every call below fails its checks first
+
+    def call(pg, n=4096, params=p):
+        return lib.ea_score_paged(ctypes.byref(params), fake, fake, ctypes.byref(pg), n, fake, fake, fake, fake,
+                                  ws_bytes, None)
+    assert call(EaPaged(0x20000, 48, 100, 100)) == 2          # not a power of two
+    assert call(EaPaged(0x20000, 16, 1000, 1000)) == 2        # below a tile of 32 keys
+    assert call(EaPaged(0x20000, 64, 10, 100)) == 1           # 10 blocks of 64 rows cannot hold 4096
+    assert call(EaPaged(0, 64, 100, 100)) == 1                # no table
+    assert call(EaPaged(0x20000, 64, 100, 0)) == 1            # empty pool
+    assert call(EaPaged(0x20000, 64, 100, 100), params=make_params(1, 4, 2, 128, EA_F32)) == 2

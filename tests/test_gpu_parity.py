@@ -719,3 +719,109 @@ def test_scores_with_output_projection(dt, d, hq, hkv, n, dm):
     P.check_scores(wnorm.cpu().numpy(), wn_ref, tol)
     ref = X.scores_wo(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), sg32.astype(np.float64), w64, 0.02)
     P.check_scores(scores.cpu().numpy(), ref, 2 * tol)
+
+
+# ------------------------------------------------------------------- paged (block-table) caches
+def _paged_setup(cfg, lay, bs, seed):
+    import torch
+    from ea_inputs import make_block_pools
+    kp, vp, tab, nb = make_block_pools(lay["k"], lay["v"], bs, seed)
+    tabd = torch.from_numpy(tab).cuda()
+    return kp, vp, tab, nb, P.to_dev(kp), P.to_dev(vp), tabd, ea.make_paged(tabd, bs, nb)
+
+
+@pytest.mark.parametrize("name,n,bs", [("c2mini", 3000, 32), ("c2mini", 2049, 256), ("c4mini", 1500, 64),
+                                      ("c5mini", 1100, 128), ("d64bf16", 700, 1024), ("c2mini", 17, 32)])
+def test_score_paged(name, n, bs):
+    """ea_score over block pools behind a shuffled block table: same scores as the oracle gives for
+    the logical rows (the rows of a sequence's last block beyond n, and the pool's spare blocks,
+    hold NaN)."""
+    import torch
+    from oracle import ea_extensions as X
+    cfg, kw = MINI[name]
+    lay = make_layer(cfg, **dict(kw, n=max(n, kw.get("window", 1) + 8)))
+    lay = dict(lay, n=n, k=np.ascontiguousarray(lay["k"][:, :, :n]), v=np.ascontiguousarray(lay["v"][:, :, :n]))
+    kp, vp, tab, nb, kd, vd, tabd, pg = _paged_setup(cfg, lay, bs, seed=n + bs)
+    assert np.array_equal(X.paged_rows(kp, tab, n), lay["k"])
+    rmu, rsg = _oracle_stats(cfg, lay)
+    mu32, sg32 = rmu.astype(np.float32), rsg.astype(np.float32)
+    p = P.params_for(cfg, epsilon=0.02)
+    ws = P.workspace(p, n, 1)
+    sc = torch.empty(cfg.batch, cfg.n_kv_heads, n, dtype=torch.float32, device="cuda")
+    ea.score_paged(p, kd, vd, pg, n, P.to_dev(mu32), P.to_dev(sg32), sc, ws)
+    torch.cuda.synchronize()
+    ref = O.scores(widen(lay["k"]), widen(lay["v"]), mu32.astype(np.float64), sg32.astype(np.float64), 0.02)
+    P.check_scores(sc.cpu().numpy(), ref, 2e-3)
+    # and agrees with the contiguous call far inside the tolerance (the two may run different
+    # kernels, which add the same fp16 products in different orders)
+    got_c = P.run_score(cfg, lay, mu32, sg32, 0.02)
+    np.testing.assert_allclose(sc.cpu().numpy(), got_c, rtol=2e-5, atol=0)
+
+
+@pytest.mark.parametrize("order_free", [0, 1])
+@pytest.mark.parametrize("name,n,bs", [("c2mini", 3000, 32), ("c4mini", 1500, 64), ("c5mini", 1100, 128)])
+def test_compress_layer_paged(name, n, bs, order_free):
+    """The whole path over a paged cache: scores, kept set and the compacted logical rows equal
+    what the oracle gives on the contiguous view; pool rows outside the kept prefix are untouched."""
+    import torch
+    from oracle import ea_extensions as X
+    cfg, kw = MINI[name]
+    lay = make_layer(cfg, **dict(kw, n=n))
+    w = lay["window"]
+    n_keep = int(n * 0.6)
+    kp, vp, tab, nb, kd, vd, tabd, pg = _paged_setup(cfg, lay, bs, seed=7 * n + bs)
+    p = P.params_for(cfg, epsilon=0.02)
+    ws = P.workspace(p, n, w)
+    sc = torch.empty(cfg.batch, cfg.n_kv_heads, n, dtype=torch.float32, device="cuda")
+    idx = torch.empty(cfg.batch, cfg.n_kv_heads, n_keep, dtype=torch.int32, device="cuda")
+    perm = torch.empty_like(idx)
+    ea.compress_layer_paged(p, P.to_dev(lay["q_win"]), w, lay["q_pos0"], P.to_dev(lay["inv_freq"]), lay["t_next"],
+                            kd, vd, pg, n, n_keep, order_free, sc, idx, perm, ws)
+    torch.cuda.synchronize()
+    ref = O.compress_layer(widen(lay["q_win"]), widen(lay["k"]), widen(lay["v"]), lay["q_pos0"], lay["inv_freq"],
+                           lay["t_next"], n_keep, T=cfg.horizon_T, epsilon=0.02, k_store=lay["k"], v_store=lay["v"])
+    gi = idx.cpu().numpy()
+    P.check_scores(sc.cpu().numpy(), ref["scores"], 2e-3)
+    P.check_idx_vs_oracle_scores(gi, ref["scores"], n_keep, 2e-3)
+    P.check_idx_exact_given_scores(gi, sc.cpu().numpy(), n_keep)
+    ka, va = X.paged_rows(P.to_host(kd), tab, n), X.paged_rows(P.to_host(vd), tab, n)
+    if order_free:
+        for b in range(cfg.batch):
+            for h in range(cfg.n_kv_heads):
+                rperm = X.unordered_perm(gi[b, h], n_keep)
+                assert np.array_equal(perm.cpu().numpy()[b, h], rperm)
+                assert np.array_equal(ka[b, h, :n_keep], lay["k"][b, h][rperm])
+                assert np.array_equal(va[b, h, :n_keep], lay["v"][b, h][rperm])
+        assert np.array_equal(ka[:, :, n_keep:], lay["k"][:, :, n_keep:])
+    else:
+        P.check_compaction(ka, va, lay["k"], lay["v"], gi, n_keep)
+    # nothing outside the sequences' own rows was written: spare blocks and block tails keep their marker
+    used = np.zeros(kp.shape[:1] + kp.shape[2:3], bool)
+    for b in range(cfg.batch):
+        for i in range(n):
+            used[tab[b, i // bs], i % bs] = True
+    assert np.array_equal(P.to_host(kd)[~used[:, None, :].repeat(cfg.n_kv_heads, 1)],
+                          kp[~used[:, None, :].repeat(cfg.n_kv_heads, 1)])
+
+
+def test_compact_paged_matches_contiguous_compaction():
+    """ea_compact_paged (in place, order-preserving) on adversarial kept sets: the logical rows
+    equal those of ea_compact on the contiguous cache."""
+    import torch
+    from oracle import ea_extensions as X
+    cfg = CONFIGS["c2"].with_(n_q_heads=8, n_kv_heads=2, batch=2)
+    n, bs = 5000, 64
+    lay = make_layer(cfg, n=n, window=8)
+    r = np.random.default_rng(3)
+    for name, keep in (("random", np.sort(r.choice(n, 2100, replace=False))), ("tail", np.arange(n - 1900, n)),
+                       ("head", np.arange(0, 1234)), ("stride", np.arange(1, n, 3))):
+        nk = len(keep)
+        idx = np.broadcast_to(keep.astype(np.int32), (cfg.batch, cfg.n_kv_heads, nk)).copy()
+        kp, vp, tab, nb, kd, vd, tabd, pg = _paged_setup(cfg, lay, bs, seed=nk)
+        p = P.params_for(cfg)
+        ws = P.workspace(p, n, 1)
+        ea.compact_paged(p, kd, vd, pg, n, P.to_dev(idx), nk, 0, None, ws)
+        torch.cuda.synchronize()
+        ka, va = X.paged_rows(P.to_host(kd), tab, n), X.paged_rows(P.to_host(vd), tab, n)
+        P.check_compaction(ka, va, lay["k"], lay["v"], idx, nk)
+        assert ea.debug_status(p, n, 1, ws) == 0, name

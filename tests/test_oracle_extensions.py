@@ -177,3 +177,20 @@ def test_scorers_on_hand_made_keys():
     kk = r.standard_normal((2, 2, 50, 16))
     assert np.allclose(X.keydiff_scores(kk), X.keydiff_scores(7.0 * kk))
     assert X.keydiff_scores(kk).min() >= 0 and X.keydiff_scores(kk).max() <= 2
+
+
+def test_paged_rows_on_a_hand_made_pool_and_against_the_generator_scatter():
+    # two sequences, one head, blocks of 2 rows, d = 1: pool rows written out by hand
+    pool = np.array([[[[10.], [11.]]], [[[20.], [21.]]], [[[30.], [31.]]], [[[40.], [41.]]]])   # [4, 1, 2, 1]
+    table = np.array([[2, 0], [3, 1]])
+    got = X.paged_rows(pool, table, 3)
+    assert got[0, 0, :, 0].tolist() == [30., 31., 10.] and got[1, 0, :, 0].tolist() == [40., 41., 20.]
+    # the generator's scatter is coded separately (block slices, not row by row): round trip
+    from ea_inputs import make_block_pools
+    rng = np.random.default_rng(5)
+    k = rng.standard_normal((2, 3, 75, 4))
+    v = rng.standard_normal((2, 3, 75, 4))
+    kp, vp, tab, nb = make_block_pools(k, v, 32, seed=11)
+    assert kp.shape == (nb, 3, 32, 4) and len(set(tab.ravel().tolist())) == tab.size
+    np.testing.assert_array_equal(X.paged_rows(kp, tab, 75), k)
+    np.testing.assert_array_equal(X.paged_rows(vp, tab, 75), v)
