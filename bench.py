@@ -54,13 +54,16 @@ def parse():
     ap.add_argument("--epsilon", type=float, default=0.02)
     ap.add_argument("--layer-batch", type=int, default=0,
                     help="consecutive layers handed to one ea_compress_layer call as a batch (0 = 4 for the "
-                         "prefill shapes, 8 for the decode schedule)")
+                         "prefill shapes, 24 for the decode schedule)")
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the calls are spread over (each with its own workspace)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (all calls, one stream) in a HIP graph and time replays of it")
     ap.add_argument("--skip-layer-by-layer", action="store_true",
                     help="leave the layer-by-layer leg out (profiling runs: every launch then has one shape)")
+    ap.add_argument("--paged", type=int, default=0, metavar="BLOCK",
+                    help="prefill shapes: keep the cache in block pools of BLOCK rows behind a shuffled block "
+                         "table and time ea_compress_layer_paged (0 = contiguous tensors)")
     ap.add_argument("--ordered", action="store_true",
                     help="decode schedule: use the order-preserving compaction instead of the order-free one")
     return ap.parse_args()
@@ -200,11 +203,39 @@ def run_prefill(a, torch, ea, cfg):
     q_pos0, t_next = n - w, n
     torch.cuda.synchronize()
 
+    pg_of = None
+    if a.paged:
+        # one pool for the whole cache: every (layer, sequence) is a sequence of the block table
+        bs = a.paged
+        assert n % bs == 0, "--paged: the block size must divide n here"
+        mb = n // bs
+        nblk = L * B * mb
+        perm = torch.randperm(nblk, device=dev, generator=torch.Generator(device=dev).manual_seed(7))
+        table = perm.to(torch.int32).reshape(L * B, mb).contiguous()
+
+        def to_pool(t):        # [L, B, Hkv, n, d] -> [nblk, Hkv, bs, d], logical block j of sequence s at perm[s*mb+j]
+            blocks = t.reshape(L * B, Hkv, mb, bs, d).permute(0, 2, 1, 3, 4).reshape(nblk, Hkv, bs, d)
+            pool = torch.empty_like(blocks)
+            pool[perm.long()] = blocks
+            return pool
+        k0p, v0p = to_pool(k0), to_pool(v0)
+        del k0, v0, k, v
+        k0, v0 = k0p, v0p
+        k, v = torch.empty_like(k0), torch.empty_like(v0)
+        pg_of = lambda l, lb: ea.make_paged(table[l * B:(l + lb) * B], bs, nblk)
+
     def restore():
         k.copy_(k0)
         v.copy_(v0)
 
+    def step_paged():
+        for i, l in enumerate(range(0, L, LB)):
+            ea.compress_layer_paged(p, q[l:l + LB], w, q_pos0, inv, t_next, k, v, pg_of(l, LB), n, n_keep, 0, None,
+                                    None, None, wss[i % ns], stream=streams[i % ns])
+
     def step():
+        if a.paged:
+            return step_paged()
         # call i runs on stream i % ns with that stream's workspace; the caller synchronises the
         # device before and after a step
         for i, l in enumerate(range(0, L, LB)):
@@ -235,6 +266,17 @@ def run_prefill(a, torch, ea, cfg):
     frac = lambda ms: pairs * bytes_per_pair / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
     layer_by_layer = None
+    if a.paged:
+        out = {"metric": "KV pairs scored+compacted/sec", "value": round(pairs / (ms_per_step * 1e-3) / 1e9, 4),
+               "unit": "G pairs/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+               "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+               "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": "%s, paged: %d layers x %d KV heads x %d tokens x d%d in pools of %d-row blocks "
+                                      "behind a shuffled block table, ratio %.2f, %d layer(s) per call, %d streams" %
+                                      (cfg.name, L, Hkv * B, n, d, a.paged, a.ratio, LB, ns),
+                          "pairs_per_step": pairs, "bytes_per_pair": bytes_per_pair},
+               "path_hbm_frac": round(frac(ms_per_step), 4)}
+        return out
     if not a.skip_layer_by_layer:
         lbl_times = timed(step_layer_by_layer, restore, max(2, min(a.steps, 3)), 1, torch)
         lbl_ms = 1e3 * sum(lbl_times) / len(lbl_times)
@@ -300,7 +342,7 @@ def run_decode(a, torch, ea, cfg):
     B, Hq, Hkv, d, w = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.window
     P0, P1, every, budget = 2048, 32768, 512, 4096
     n_cap = budget + every
-    LB = max(1, a.layer_batch or 8)
+    LB = max(1, a.layer_batch or 24)
     while L % LB:
         LB -= 1
     p = ea.make_params(B * LB, Hq, Hkv, d, ea.EA_BF16, horizon_T=cfg.horizon_T, epsilon=a.epsilon)
