@@ -7,4 +7,4 @@ the oracle nor the HIP library imports it: callers pass its arrays to both.
 """
 from .configs import CacheConfig, CONFIGS, get_config          # noqa: F401
 from .host import (make_layer, bf16_bits_from_f64, f64_from_bf16_bits,  # noqa: F401
-                   inv_freq_table, layer_seed, widen, make_block_pools)
+                   inv_freq_table, layer_seed, widen, make_block_pools, quantize_fp8)

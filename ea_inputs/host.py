@@ -152,3 +152,15 @@ def make_block_pools(k, v, block_size, seed, spare_blocks=3):
                 pool[table[b, j], :, :rows.shape[1]] = rows
         pools.append(pool)
     return pools[0], pools[1], table, num_blocks
+
+
+def quantize_fp8(x, headroom=0.9):
+    """Stores x [B, H, n, d] (float64) as OCP e4m3 bytes with one fp32 scale per (b, h): the head's
+    largest magnitude lands at `headroom` x 448.  The rounding is torch's float8_e4m3fn conversion
+    (a library routine; the oracle decodes the bytes with code of its own).  Returns (uint8 bytes,
+    float32 scales [B, H])."""
+    import torch
+    amax = np.abs(x).max(axis=(2, 3))
+    scale = (np.maximum(amax, 1e-30) / (448.0 * headroom)).astype(np.float32)
+    y = torch.from_numpy(x / scale.astype(np.float64)[:, :, None, None]).to(torch.float32)
+    return y.to(torch.float8_e4m3fn).view(torch.uint8).numpy(), scale

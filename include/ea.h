@@ -51,7 +51,11 @@ typedef enum {
   EA_ERR_DEVICE = 4        /* a kernel launch failed (hipGetLastError)                        */
 } ea_status;
 
-typedef enum { EA_F32 = 0, EA_BF16 = 1 } ea_dtype;
+typedef enum {
+  EA_F32 = 0,
+  EA_BF16 = 1,
+  EA_FP8_E4M3 = 2 /* rows of d bytes: accepted by ea_compact and ea_compact_unordered only (see ea_score_fp8) */
+} ea_dtype;
 
 typedef struct {
   int32_t batch;        /* B  >= 1                                                          */
@@ -234,6 +238,25 @@ ea_status ea_compress_layer_paged(const ea_params* p, const void* q_win, int64_t
                                   const ea_paged* pg, int64_t n, int64_t n_keep, int32_t order_free,
                                   float* scores_out, int32_t* idx_out, int32_t* perm_out, void* ws,
                                   size_t ws_bytes, void* stream);
+
+/* Caches stored in 8 bits (Related Works, "Quantization": orthogonal to eviction, the two combine).
+ * k8, v8 [B, Hkv, n_cap, d] hold OCP e4m3 ("float8_e4m3fn") bytes and the real key / value is
+ * k_scale[b,h] * k8[b,h] / v_scale[b,h] * v8[b,h]  (k_scale, v_scale: fp32 DEVICE [B, Hkv], NULL = 1).
+ * ea_score_fp8 and ea_compress_layer_fp8 are ea_score and ea_compress_layer over such a cache
+ * (order_free / perm_out as for ea_compress_layer_paged): the bytes widen exactly to the fp16
+ * operands of the matrix cores, so the arithmetic is that of the bf16 path on the dequantised
+ * values.  p->dtype is the type of q_win and must be EA_BF16; head_dim 128 or 256 (else
+ * EA_ERR_UNSUPPORTED).  The compaction calls move rows without looking into them: for ea_compact
+ * and ea_compact_unordered on such a cache set p->dtype = EA_FP8_E4M3 (rows of d bytes); the scales
+ * belong to the head and do not move. */
+ea_status ea_score_fp8(const ea_params* p, const void* k8, const void* v8, const float* k_scale,
+                       const float* v_scale, int64_t n, int64_t n_cap, const float* mu, const float* sigma,
+                       float* scores, void* ws, size_t ws_bytes, void* stream);
+ea_status ea_compress_layer_fp8(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                                const double* inv_freq, int64_t t_next, void* k8, void* v8,
+                                const float* k_scale, const float* v_scale, int64_t n, int64_t n_cap,
+                                int64_t n_keep, int32_t order_free, float* scores_out, int32_t* idx_out,
+                                int32_t* perm_out, void* ws, size_t ws_bytes, void* stream);
 
 /* Listing 1: int(n * (1 - ratio)) in IEEE double, truncated toward zero; -1 if ratio is
  * outside [0, 1] or n < 0.  Host only. */

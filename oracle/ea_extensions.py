@@ -11,6 +11,7 @@ cpu_baseline leg may import it; it shares nothing with the HIP library).
   query_stats_hidden     Eq. 5 as printed: statistics of the hidden states, pushed through W_Q
   scores_wo              Eq. 9 as printed: ||W_o v|| instead of ||v||
   paged_rows             block-table ("paged") cache layout: which pool row holds a logical row
+  fp8_e4m3_decode        caches stored as OCP e4m3 bytes: the value of every byte
   knorm / streaming / keydiff scores   the comparison scorers of Sec. 3.1 ("Baselines"), from the one
                          sentence the paper gives each, on the same select + compact back half
 
@@ -35,7 +36,8 @@ scores reduce to the per-head rule); hidden-state statistics vs the projected-qu
 ea_oracle.query_stats (Eq. 5's linearity); ||W_o v|| vs numpy.linalg.norm of the explicit product
 and the W_o = I reduction to ea_oracle.scores; the scorers vs their one-line definitions on
 hand-made keys; the paged layout vs a pool written out by hand and vs the input generator's
-separately coded scatter.
+separately coded scatter; the e4m3 decoding vs values written out from the format's definition
+and vs torch's float8_e4m3fn for all 256 codes.
 """
 import math
 
@@ -198,3 +200,15 @@ def paged_rows(pool, table, n):
         for i in range(n):
             out[b, :, i] = pool[table[b, i // bs], :, i % bs]
     return out
+
+
+# ------------------------------------------------------------------ caches stored as e4m3 bytes (f3)
+def fp8_e4m3_decode(b):
+    """Value of OCP e4m3 ("float8_e4m3fn") bytes as float64: 1 sign bit, 4 exponent bits (bias 7),
+    3 mantissa bits; exponent 0 is subnormal ((m / 8) * 2^-6); there are no infinities and
+    S.1111.111 is NaN, so the largest magnitude is 1.75 * 2^8 = 448."""
+    b = np.asarray(b, np.uint8).astype(np.int64)
+    sign = np.where(b >> 7, -1.0, 1.0)
+    e, m = (b >> 3) & 15, b & 7
+    mag = np.where(e == 0, (m / 8.0) * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    return np.where((e == 15) & (m == 7), np.nan, sign * mag)

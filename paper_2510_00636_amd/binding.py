@@ -5,7 +5,7 @@ torch.cuda.Stream, a raw hipStream_t integer, or None for torch's current stream
 import ctypes
 import os
 
-EA_F32, EA_BF16 = 0, 1
+EA_F32, EA_BF16, EA_FP8_E4M3 = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
@@ -86,6 +86,11 @@ def load_library():
     lib.ea_compress_layer_paged.restype = ctypes.c_int
     lib.ea_compress_layer_paged.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, PG, I64, I64, ctypes.c_int32,
                                             VP, VP, VP, VP, SZ, VP]
+    lib.ea_score_fp8.restype = ctypes.c_int
+    lib.ea_score_fp8.argtypes = [P, VP, VP, VP, VP, I64, I64, VP, VP, VP, VP, SZ, VP]
+    lib.ea_compress_layer_fp8.restype = ctypes.c_int
+    lib.ea_compress_layer_fp8.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, VP, VP, I64, I64, I64, ctypes.c_int32,
+                                          VP, VP, VP, VP, SZ, VP]
     lib.ea_compress_layer_timed.restype = ctypes.c_int
     lib.ea_compress_layer_timed.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, SZ, VP,
                                             ctypes.POINTER(ctypes.c_float)]
@@ -265,6 +270,21 @@ def compress_layer_paged(p, q_win, window, q_pos0, inv_freq, t_next, k_pool, v_p
                                                   ctypes.byref(pg), int(n), int(n_keep_), int(order_free),
                                                   _ptr(scores_out), _ptr(idx_out), _ptr(perm_out), _ptr(ws),
                                                   _nbytes(ws), _stream(stream)), "ea_compress_layer_paged")
+
+
+def score_fp8(p, k8, v8, k_scale, v_scale, n, n_cap, mu, sigma, scores, ws, stream=None):
+    _check(load_library().ea_score_fp8(ctypes.byref(p), _ptr(k8), _ptr(v8), _ptr(k_scale), _ptr(v_scale), int(n),
+                                       int(n_cap), _ptr(mu), _ptr(sigma), _ptr(scores), _ptr(ws), _nbytes(ws),
+                                       _stream(stream)), "ea_score_fp8")
+
+
+def compress_layer_fp8(p, q_win, window, q_pos0, inv_freq, t_next, k8, v8, k_scale, v_scale, n, n_cap, n_keep_,
+                       order_free, scores_out, idx_out, perm_out, ws, stream=None):
+    _check(load_library().ea_compress_layer_fp8(ctypes.byref(p), _ptr(q_win), int(window), int(q_pos0),
+                                                _ptr(inv_freq), int(t_next), _ptr(k8), _ptr(v8), _ptr(k_scale),
+                                                _ptr(v_scale), int(n), int(n_cap), int(n_keep_), int(order_free),
+                                                _ptr(scores_out), _ptr(idx_out), _ptr(perm_out), _ptr(ws),
+                                                _nbytes(ws), _stream(stream)), "ea_compress_layer_fp8")
 
 
 N_STAGES = 6

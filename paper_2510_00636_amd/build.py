@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libea.so")
 SOURCES = ["ea_host.cpp", "ea_api.hip", "ea_stats.hip", "ea_score.hip", "ea_score_d64.hip", "ea_score_d128.hip", "ea_score_d128b.hip",
-           "ea_score_d256.hip", "ea_score_hw.hip", "ea_select.hip",
+           "ea_score_d256.hip", "ea_score_fp8.hip", "ea_score_fp8b.hip", "ea_score_hw.hip", "ea_select.hip",
            "ea_compact.hip", "ea_baselines.hip", "ea_frontend.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off for the device pass (the host pass warns that it

@@ -58,7 +58,7 @@ static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t 
                            const float* mu, const float* sigma, float* scores, uint32_t* hist0,
                            bool hist_zeroed, char* ws, const WsLayout& L, hipStream_t st,
                            hipEvent_t* ev = nullptr, const float* wnorm = nullptr, float* wnorm_out = nullptr,
-                           const PageMap* pm = nullptr) {
+                           const PageMap* pm = nullptr, const float* kscale = nullptr, const float* vscale = nullptr) {
   // wnorm: Eq. 9 with per-query-head norms ||W_o v||.  wnorm_out: stop after pass A and turn its
   // quadratic forms into such norms (the caller passed the values as keys, mu = 0, Sigma = M_g).
   float* vnorm = (float*)(ws + L.vnorm);
@@ -72,7 +72,7 @@ static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t 
     if (ev) EA_TRY(hipEventRecord(ev[0], st));
     EA_TRY(launch_score_mfma(d, sp, k, v, n, n_cap, frags, post, (float*)(ws + L.logits), vnorm,
                              (float2*)(ws + L.part), hist + 2 * kSelBins + kTicketSlot, 3 * kSelBins,
-                             st, pm));
+                             st, pm, kscale, vscale));
     if (ev) EA_TRY(hipEventRecord(ev[1], st));
     if (wnorm_out) return launch_wnorm(ws + L.logits, 0, (size_t)d.qheads() * n, d.D, wnorm_out, st) == hipSuccess
                               ? EA_OK : EA_ERR_DEVICE;
@@ -273,7 +273,7 @@ ea_status ea_compact(const ea_params* p, const void* k, const void* v, int64_t n
                      const int32_t* idx, int64_t n_keep, void* k_out, void* v_out, void* ws,
                      size_t ws_bytes, void* stream) {
   Dims d;
-  ea_status s = check_params(p, &d);
+  ea_status s = check_params(p, &d, true);
   if (s != EA_OK) return s;
   if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
     return EA_ERR_INVALID_ARG;
@@ -326,10 +326,16 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
                                void* v, int64_t n, int64_t n_cap, int64_t n_keep, float* scores_out,
                                int32_t* idx_out, void* ws, size_t ws_bytes, void* stream,
                                hipEvent_t* ev, bool unordered = false, int32_t* perm_out = nullptr,
-                               const PageMap* pm = nullptr) {
+                               const PageMap* pm = nullptr, bool fp8 = false, const float* kscale = nullptr,
+                               const float* vscale = nullptr) {
   Dims d;
   ea_status s = check_params(p, &d);
   if (s != EA_OK) return s;
+  if (fp8) {
+    if (d.dtype != EA_BF16 || d.D == 64) return EA_ERR_UNSUPPORTED;
+    if ((kscale && ((uintptr_t)kscale & 3u)) || (vscale && ((uintptr_t)vscale & 3u))) return EA_ERR_INVALID_ARG;
+    d.kv_fp8 = 1;
+  }
   if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || k == v || !inv_freq ||
       ((uintptr_t)inv_freq & 7u))
     return EA_ERR_INVALID_ARG;
@@ -360,7 +366,7 @@ static ea_status compress_impl(const ea_params* p, const void* q_win, int64_t wi
   if (ev) EA_TRY(hipEventRecord(ev[1], st));
   if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores,
                      n_keep > 0 && !select_in_one_launch(n) ? hist : nullptr, true, w, L, st,
-                     ev ? ev + 2 : nullptr, nullptr, nullptr, pm)) != EA_OK)
+                     ev ? ev + 2 : nullptr, nullptr, nullptr, pm, kscale, vscale)) != EA_OK)
     return s;
   if (ev) EA_TRY(hipEventRecord(ev[4], st));
   if (n_keep > 0)
@@ -461,7 +467,7 @@ ea_status ea_score_baseline(const ea_params* p, int32_t scorer, const void* k, i
 ea_status ea_compact_unordered(const ea_params* p, void* k, void* v, int64_t n, int64_t n_cap,
                                const int32_t* idx, int64_t n_keep, int32_t* perm_out, void* stream) {
   Dims d;
-  ea_status s = check_params(p, &d);
+  ea_status s = check_params(p, &d, true);
   if (s != EA_OK) return s;
   if (!aligned16(k) || !aligned16(v) || k == v) return EA_ERR_INVALID_ARG;
   if (n < 1 || n > n_cap || n > kMaxN || n_keep < 0 || n_keep > n) return EA_ERR_INVALID_ARG;
@@ -546,6 +552,34 @@ ea_status ea_compress_layer_paged(const ea_params* p, const void* q_win, int64_t
   return compress_impl(p, q_win, window, q_pos0, inv_freq, t_next, k_pool, v_pool, n, n, n_keep, scores_out,
                        idx_out, ws, ws_bytes, stream, nullptr, order_free != 0, order_free ? perm_out : nullptr,
                        &pm);
+}
+
+ea_status ea_score_fp8(const ea_params* p, const void* k8, const void* v8, const float* k_scale,
+                       const float* v_scale, int64_t n, int64_t n_cap, const float* mu, const float* sigma,
+                       float* scores, void* ws, size_t ws_bytes, void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (d.dtype != EA_BF16 || d.D == 64) return EA_ERR_UNSUPPORTED;
+  if (!aligned16(k8) || !aligned16(v8) || !aligned16(mu) || !aligned16(sigma) || !aligned16(scores))
+    return EA_ERR_INVALID_ARG;
+  if ((k_scale && ((uintptr_t)k_scale & 3u)) || (v_scale && ((uintptr_t)v_scale & 3u))) return EA_ERR_INVALID_ARG;
+  if (n < 1 || n > n_cap || n > kMaxN) return EA_ERR_INVALID_ARG;
+  d.kv_fp8 = 1;
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  return run_score(d, k8, v8, n, n_cap, mu, sigma, scores, nullptr, false, (char*)ws, L, (hipStream_t)stream,
+                   nullptr, nullptr, nullptr, nullptr, k_scale, v_scale);
+}
+
+ea_status ea_compress_layer_fp8(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                                const double* inv_freq, int64_t t_next, void* k8, void* v8,
+                                const float* k_scale, const float* v_scale, int64_t n, int64_t n_cap,
+                                int64_t n_keep, int32_t order_free, float* scores_out, int32_t* idx_out,
+                                int32_t* perm_out, void* ws, size_t ws_bytes, void* stream) {
+  return compress_impl(p, q_win, window, q_pos0, inv_freq, t_next, k8, v8, n, n_cap, n_keep, scores_out, idx_out,
+                       ws, ws_bytes, stream, nullptr, order_free != 0, order_free ? perm_out : nullptr, nullptr,
+                       true, k_scale, v_scale);
 }
 
 ea_status ea_compress_layer_timed(const ea_params* p, const void* q_win, int64_t window,

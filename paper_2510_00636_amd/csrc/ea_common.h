@@ -19,9 +19,10 @@ struct Dims {
   int B, Hq, Hkv, G, D, half;
   int dtype, rope_layout, q_is_rotated, ddof, T;
   float eps;
+  int kv_fp8;     // 1: K and V rows are e4m3 bytes (dtype then describes q_win only)
   int units() const { return B * Hkv; }
   int qheads() const { return B * Hq; }
-  int esize() const { return dtype == EA_BF16 ? 2 : 4; }
+  int esize() const { return kv_fp8 ? 1 : dtype == EA_BF16 ? 2 : 4; }    // of a cached element
 };
 
 // How the matrix-core score kernel is tiled for one (d, G): heads per pass, passes, waves.
@@ -54,7 +55,8 @@ struct WsLayout {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-ea_status check_params(const ea_params* p, Dims* d);
+// rows_only: the call only moves cache rows, so p->dtype may also be EA_FP8_E4M3
+ea_status check_params(const ea_params* p, Dims* d, bool rows_only = false);
 // paged: the caches are block pools (the register-fragment kernel does not read those)
 ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu, int paged = 0);
 WsLayout make_ws_layout(const Dims& d, int64_t n, int64_t window);

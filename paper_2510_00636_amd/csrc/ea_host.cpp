@@ -6,7 +6,7 @@
 
 namespace ea {
 
-ea_status check_params(const ea_params* p, Dims* d) {
+ea_status check_params(const ea_params* p, Dims* d, bool rows_only) {
   if (!p) return EA_ERR_INVALID_ARG;
   if (p->batch < 1 || p->n_kv_heads < 1 || p->n_q_heads < 1) return EA_ERR_INVALID_ARG;
   if (p->n_q_heads % p->n_kv_heads != 0) return EA_ERR_INVALID_ARG;
@@ -15,8 +15,10 @@ ea_status check_params(const ea_params* p, Dims* d) {
   if (p->q_is_rotated != 0 && p->q_is_rotated != 1) return EA_ERR_INVALID_ARG;
   if (p->horizon_T < 1) return EA_ERR_INVALID_ARG;
   if (!(p->epsilon >= 0.0f) || !isfinite(p->epsilon)) return EA_ERR_INVALID_ARG;
-  if (p->dtype != EA_F32 && p->dtype != EA_BF16) return EA_ERR_UNSUPPORTED;
+  const bool fp8 = p->dtype == EA_FP8_E4M3;
+  if (p->dtype != EA_F32 && p->dtype != EA_BF16 && !(fp8 && rows_only)) return EA_ERR_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128 && p->head_dim != 256) return EA_ERR_UNSUPPORTED;
+  if (fp8 && p->head_dim == 64) return EA_ERR_UNSUPPORTED;
   int G = p->n_q_heads / p->n_kv_heads;
   if (G > 64) return EA_ERR_UNSUPPORTED;
   if ((int64_t)p->batch * p->n_q_heads > (1 << 20)) return EA_ERR_UNSUPPORTED;
@@ -26,7 +28,8 @@ ea_status check_params(const ea_params* p, Dims* d) {
   d->G = G;
   d->D = p->head_dim;
   d->half = p->head_dim / 2;
-  d->dtype = p->dtype;
+  d->dtype = fp8 ? (int)EA_BF16 : p->dtype;
+  d->kv_fp8 = fp8 ? 1 : 0;
   d->rope_layout = p->rope_layout;
   d->q_is_rotated = p->q_is_rotated;
   d->ddof = p->cov_ddof;
@@ -42,7 +45,7 @@ ScorePlan make_score_plan(const Dims& d, int64_t n, int num_cu, int paged) {
   s.hw = 0;
   s.tpt = 1;
   s.lse_pass = 0;
-  if (!paged && d.D == 128 && d.dtype == EA_BF16 && d.G % 4 == 0 && n >= 2048 && (int64_t)d.units() * (d.G / 4) <= 8) {
+  if (!paged && !d.kv_fp8 && d.D == 128 && d.dtype == EA_BF16 && d.G % 4 == 0 && n >= 2048 && (int64_t)d.units() * (d.G / 4) <= 8) {
     // groups of four query heads at d = 128, calls of up to 8 (KV head, group) units: fragments in
     // registers, one wavefront per head, two workgroups of four wavefronts per CU.  Measured per
     // layer of 8 KV heads x 131072 keys: 128 us against 129 us for the LDS-fragment kernel and a
@@ -149,7 +152,7 @@ extern "C" {
 
 size_t ea_workspace_bytes(const ea_params* p, int64_t n, int64_t window) {
   ea::Dims d;
-  if (ea::check_params(p, &d) != EA_OK) return 0;
+  if (ea::check_params(p, &d, true) != EA_OK) return 0;
   if (n < 1 || n > ea::kMaxN || window < 1 || window > ea::kMaxWindow) return 0;
   return ea::make_ws_layout(d, n, window).total;
 }

@@ -28,7 +28,9 @@ hipError_t launch_prep_frags(const Dims& d, const ScorePlan& sp, const float* mu
 hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
                              float* logits, float* vnorm, float2* part, uint32_t* tickets,
-                             int ticket_stride, hipStream_t st, const PageMap* pm = nullptr);
+                             int ticket_stride, hipStream_t st, const PageMap* pm = nullptr,
+                             const float* kscale = nullptr, const float* vscale = nullptr);
+// kscale, vscale [units] (nullable): per-head scales of caches stored as e4m3 bytes (d.kv_fp8)
 hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                             const float* mu, const float* sigma, double* logits, float* vnorm,
                             double2* part, int* nchunk_out, hipStream_t st);

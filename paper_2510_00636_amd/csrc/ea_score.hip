@@ -14,9 +14,12 @@ namespace ea {
 hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, const void* v,
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
                              float* logits, float* vnorm, float2* part, uint32_t* tickets,
-                             int ticket_stride, hipStream_t st, const PageMap* pm) {
+                             int ticket_stride, hipStream_t st, const PageMap* pm, const float* kscale,
+                             const float* vscale) {
   ScoreArgs a;
   a.pm = pm ? *pm : PageMap{nullptr, 0, 0, 1, 0};
+  a.kscale = kscale;
+  a.vscale = vscale;
   a.k = (const u32x4*)k;
   a.v = (const u32x4*)v;
   a.n = n;
@@ -35,6 +38,7 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
   a.nfrag = sp.nfrag;
   a.tickets = tickets;
   a.ticket_stride = ticket_stride;
+  if (d.kv_fp8) return launch_score_mfma_fp8(d.D, a, sp, st);
   if (sp.hw) return launch_score_hw(a, sp, st);
   switch (d.D) {
     case 64: return launch_score_mfma_d64(a, sp, st);

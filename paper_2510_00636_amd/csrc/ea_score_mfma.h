@@ -37,6 +37,8 @@ struct ScoreArgs {
   uint32_t* tickets;      // tickets + unit * ticket_stride + pass * kTicketWays + way: tile counters, zero at launch
   int ticket_stride;
   PageMap pm;             // pm.table != nullptr: k and v are block pools (CLAMP instances only)
+  const float* kscale;    // FP8 instances: real key = kscale[unit] * stored value (nullptr: 1)
+  const float* vscale;    // likewise for the values
 };
 
 __device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
@@ -50,6 +52,39 @@ __device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
   o[0] = a[0]; o[1] = a[1]; o[2] = b[0]; o[3] = b[1];
   o[4] = c[0]; o[5] = c[1]; o[6] = d[0]; o[7] = d[1];
   return o;
+}
+
+// 16 fp8 (OCP e4m3) values -> two half8: exact (a 4-bit significand and an exponent range of
+// 2^-9 .. 448 both fit fp16)
+__device__ __forceinline__ void fp8x16_to_half8x2(u32x4 r, half8& lo, half8& hi) {
+  auto lo2 = [](uint32_t w) {          // bytes 0, 1 of the word
+    const auto f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+    return __builtin_amdgcn_cvt_pkrtz(f[0], f[1]);
+  };
+  auto hi2 = [](uint32_t w) {          // bytes 2, 3
+    const auto f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+    return __builtin_amdgcn_cvt_pkrtz(f[0], f[1]);
+  };
+  const uint32_t w0 = r[0], w1 = r[1], w2 = r[2], w3 = r[3];
+  const auto a = lo2(w0), b = hi2(w0), c = lo2(w1), d = hi2(w1);
+  const auto e = lo2(w2), f = hi2(w2), g = lo2(w3), h = hi2(w3);
+  lo[0] = a[0]; lo[1] = a[1]; lo[2] = b[0]; lo[3] = b[1]; lo[4] = c[0]; lo[5] = c[1]; lo[6] = d[0]; lo[7] = d[1];
+  hi[0] = e[0]; hi[1] = e[1]; hi[2] = f[0]; hi[3] = f[1]; hi[4] = g[0]; hi[5] = g[1]; hi[6] = h[0]; hi[7] = h[1];
+}
+
+__device__ __forceinline__ float sumsq_fp8x16(u32x4 r) {
+  float s = 0.f;
+  const uint32_t w[4] = {r[0], r[1], r[2], r[3]};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const auto a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+    const auto b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+    s = fmaf(a[0], a[0], s);
+    s = fmaf(a[1], a[1], s);
+    s = fmaf(b[0], b[0], s);
+    s = fmaf(b[1], b[1], s);
+  }
+  return s;
 }
 
 __device__ __forceinline__ float sumsq_bf16x8(u32x4 r) {
@@ -161,11 +196,17 @@ constexpr int load_slot(int i) { return NX + (i * (NS - NX)) / (2 * NL); }
 // instead (per-lane row offsets, a few more vector instructions per tile): it serves heads
 // shorter than one tile (n < 32) and paged caches, where a tile must not leave its block (tiles
 // then start at multiples of 32 and the block size is a multiple of 32).
-template <int D, int GH, int NW, bool CLAMP>
+//
+// FP8 instances read caches stored as OCP e4m3 bytes with one fp32 scale per (sequence, KV head):
+// a 16-byte chunk then holds 16 channels (two k-steps of a lane), rows are half as long, the
+// staging takes half the phases, and the scales go into the per-head post factors (k_scale on
+// the linear term, its square on the quadratic one) and onto the value norm.
+template <int D, int GH, int NW, bool CLAMP, bool FP8 = false>
 __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   constexpr int NKS = D / 16, NJT = D / 32, NF = NJT * (NJT + 1);
   constexpr int NFRAG = GH * NF + 2 * NKS;
-  constexpr int CPR = D / 8;            // 16-byte chunks per row
+  constexpr int EPC = FP8 ? 16 : 8;     // channels per 16-byte chunk
+  constexpr int CPR = D / EPC;          // 16-byte chunks per row
   constexpr int RPL = 64 / CPR;         // rows per wave-wide load
   constexpr int NL = 32 / RPL;          // wave-wide loads per 32-key tile
   // Two query heads at d = 256: their triangular fragments fill 144 of the 160 KiB of LDS, so the
@@ -173,9 +214,10 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   // in four phases through a 4 KiB slab per wave.  Both heads then share one pass over K: every
   // key is loaded, converted and staged once, and the extra tile is computed once for both.
   constexpr bool XR = D == 256 && GH == 2;
-  constexpr int NPH = XR ? 4 : 2;       // staging phases per tile
+  constexpr int NPH = (XR ? 4 : 2) / (FP8 ? 2 : 1);   // staging phases per tile
   constexpr int NLF = XR ? GH * NF : NFRAG;   // fragments held in LDS
-  constexpr int NKH = NKS / NPH;        // k-steps staged per phase
+  constexpr int CH = CPR / 2;           // chunks per half row (the half a lane holds as B operands)
+  constexpr int CPP = CH / NPH;         // of those, staged per phase
   constexpr int RP = CPR / NPH;         // staged chunks per row and phase
   constexpr int RPS = 16 / RP;          // staged rows per 256 bytes (one sweep of the LDS banks)
   extern __shared__ u32x4 smem[];
@@ -234,11 +276,13 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     for (int i = 0; i < 2 * NKS; ++i) xf[i] = __builtin_bit_cast(half8, fsrc[(GH * NF + i) * 64 + lane]);
   }
   float pq[GH], pm[GH];
+  const float ks = (FP8 && a.kscale) ? a.kscale[unit] : 1.0f;
+  const float vs2 = (FP8 && a.vscale) ? a.vscale[unit] * a.vscale[unit] : 1.0f;
 #pragma unroll
   for (int g = 0; g < GH; ++g) {
     const bool ok = g0 + g < a.G;
-    pq[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 0] : 0.f;
-    pm[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 1] : 0.f;
+    pq[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 0] * (ks * ks) : 0.f;
+    pm[g] = ok ? a.post[((size_t)unit * a.G + g0 + g) * 2 + 1] * ks : 0.f;
   }
 
   const int r = lane & 31, hh = lane >> 5;
@@ -338,7 +382,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     if (do_v) {
       const long long row = b0 + lch * RPL + lrow;
       if (lch < NL && row >= key_prev && row < a.n)
-        a.vnorm[(size_t)unit * a.n + row] = __builtin_amdgcn_sqrtf(vsq_prev);
+        a.vnorm[(size_t)unit * a.n + row] = __builtin_amdgcn_sqrtf(FP8 ? vsq_prev * vs2 : vsq_prev);
     }
   };
 
@@ -348,8 +392,8 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     half8 Kh[NKS];
 #pragma unroll
     for (int hf = 0; hf < NPH; ++hf) {
-      if (((lch % NKS) / NKH) == hf) {
-        const int sc = (lch / NKS) * NKH + (lch % NKH);
+      if (((lch % CH) / CPP) == hf) {
+        const int sc = (lch / CH) * CPP + (lch % CPP);
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
           const int rho = j * RPL + lrow;
@@ -359,9 +403,11 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int q = 0; q < NKH; ++q) {
-        const int sc = hh * NKH + q;
-        Kh[hf * NKH + q] = bf16x8_to_half8(stg[r * RP + (sc ^ ((r / RPS) & (RP - 1)))]);
+      for (int q = 0; q < CPP; ++q) {
+        const int sc = hh * CPP + q;
+        const u32x4 piece = stg[r * RP + (sc ^ ((r / RPS) & (RP - 1)))];
+        if constexpr (FP8) fp8x16_to_half8x2(piece, Kh[2 * (hf * CPP + q)], Kh[2 * (hf * CPP + q) + 1]);
+        else Kh[hf * CPP + q] = bf16x8_to_half8(piece);
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -459,7 +505,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
         // returned long before it is read.
         if constexpr (f == NL) t_nxt_raw = grab();
         if constexpr (f < NL) {                   // V chunk f: lane lch == f keeps its row's sum
-          const float ss = group_sum<CPR>(sumsq_bf16x8(vraw[f]));
+          const float ss = group_sum<CPR>(FP8 ? sumsq_fp8x16(vraw[f]) : sumsq_bf16x8(vraw[f]));
           vsq = lch == f ? ss : vsq;
         }
         if constexpr (f == NX + 1) {              // rows of the extra tile, two steps after its end
@@ -510,9 +556,10 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
 
 }
 
-template <int D, int GH, int NW, bool CLAMP>
+template <int D, int GH, int NW, bool CLAMP, bool FP8 = false>
 inline hipError_t launch_one(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st) {
-  auto kern = k_score_mfma<D, GH, NW, CLAMP>;
+  static_assert(!FP8 || D >= 128, "fp8 rows of 64 channels are not covered");
+  auto kern = k_score_mfma<D, GH, NW, CLAMP, FP8>;
   static LdsOptIn opt;                    // one per kernel instance
   hipError_t e = opt.ensure(reinterpret_cast<const void*>(kern), sp.lds_bytes);
   if (e != hipSuccess) return e;
@@ -528,6 +575,9 @@ hipError_t launch_score_mfma_d64(const ScoreArgs& a, const ScorePlan& sp, hipStr
 hipError_t launch_score_mfma_d128(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
 hipError_t launch_score_mfma_d128b(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
 hipError_t launch_score_mfma_d256(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
+// ea_score_fp8.hip: the instances for caches stored as e4m3 bytes (d = 128 and 256)
+hipError_t launch_score_mfma_fp8(int D, const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
+hipError_t launch_score_mfma_fp8b(int D, const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
 // ea_score_hw.hip: fragments in registers, one wavefront per query head (d = 128, groups of four)
 hipError_t launch_score_hw(const ScoreArgs& a, const ScorePlan& sp, hipStream_t st);
 

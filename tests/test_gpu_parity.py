@@ -825,3 +825,106 @@ def test_compact_paged_matches_contiguous_compaction():
         ka, va = X.paged_rows(P.to_host(kd), tab, n), X.paged_rows(P.to_host(vd), tab, n)
         P.check_compaction(ka, va, lay["k"], lay["v"], idx, nk)
         assert ea.debug_status(p, n, 1, ws) == 0, name
+
+
+# ------------------------------------------------------------------- caches stored as e4m3 bytes
+def _fp8_layer(cfg, n, window, pos0=None):
+    """A generated layer whose K and V are then stored as e4m3 bytes with per-head scales; the
+    oracle sees the dequantised values (its own decoding of the bytes times the scales)."""
+    from ea_inputs import quantize_fp8
+    from oracle import ea_extensions as X
+    kw = dict(n=n, window=window)
+    if pos0 is not None:
+        kw["pos0"] = pos0
+    lay = make_layer(cfg, **kw)
+    k8, ks = quantize_fp8(widen(lay["k"]))
+    v8, vs = quantize_fp8(widen(lay["v"]))
+    kd = X.fp8_e4m3_decode(k8) * ks.astype(np.float64)[:, :, None, None]
+    vd = X.fp8_e4m3_decode(v8) * vs.astype(np.float64)[:, :, None, None]
+    return lay, k8, v8, ks, vs, kd, vd
+
+
+@pytest.mark.parametrize("name,hq,hkv,n", [("c2", 8, 2, 3000), ("c2", 5, 1, 1100), ("c2", 3, 1, 2049), ("c2", 2, 2, 700),
+                                           ("c2", 1, 1, 20), ("c4", 2, 1, 1500), ("c4", 1, 1, 900), ("c4", 3, 1, 777)])
+def test_score_fp8(name, hq, hkv, n):
+    """ea_score_fp8 against the oracle on the dequantised cache: every group size the kernels
+    instantiate at d = 128 and 256, ragged sizes, a head shorter than a tile; NaN rows beyond n."""
+    import torch
+    cfg = CONFIGS[name].with_(batch=2 if n > 1000 else 1, n_q_heads=hq, n_kv_heads=hkv)
+    lay, k8, v8, ks, vs, kd, vd = _fp8_layer(cfg, max(n, 40), 16)
+    k8, v8, kd, vd = k8[:, :, :n], v8[:, :, :n], kd[:, :, :n], vd[:, :, :n]
+    lay = dict(lay, n=n)
+    rmu, rsg = _oracle_stats(cfg, lay)
+    mu32, sg32 = rmu.astype(np.float32), rsg.astype(np.float32)
+    n_cap = n + 11
+    pad = [(0, 0), (0, 0), (0, n_cap - n), (0, 0)]
+    k8p, v8p = np.pad(k8, pad, constant_values=0x7F), np.pad(v8, pad, constant_values=0x7F)     # NaN codes
+    p = P.params_for(cfg, epsilon=0.02)
+    ws = P.workspace(p, n, 1)
+    sc = torch.empty(cfg.batch, hkv, n, dtype=torch.float32, device="cuda")
+    ea.score_fp8(p, torch.from_numpy(k8p).cuda(), torch.from_numpy(v8p).cuda(), torch.from_numpy(ks).cuda(),
+                 torch.from_numpy(vs).cuda(), n, n_cap, P.to_dev(mu32), P.to_dev(sg32), sc, ws)
+    torch.cuda.synchronize()
+    ref = O.scores(kd, vd, mu32.astype(np.float64), sg32.astype(np.float64), 0.02)
+    P.check_scores(sc.cpu().numpy(), ref, 2e-3)
+
+
+@pytest.mark.parametrize("order_free", [0, 1])
+@pytest.mark.parametrize("name,n,w", [("c2", 3000, 128), ("c4", 1500, 64), ("c5", 1100, 512)])
+def test_compress_layer_fp8(name, n, w, order_free):
+    import torch
+    from oracle import ea_extensions as X
+    cfg = CONFIGS[name].with_(batch=1) if name == "c4" else CONFIGS[name]
+    lay, k8, v8, ks, vs, kd, vd = _fp8_layer(cfg, n, w, pos0=30000 if name == "c5" else None)
+    n_keep = int(n * 0.55)
+    p = P.params_for(cfg, epsilon=0.02)
+    ws = P.workspace(p, n, w)
+    k8d, v8d = torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda()
+    sc = torch.empty(cfg.batch, cfg.n_kv_heads, n, dtype=torch.float32, device="cuda")
+    idx = torch.empty(cfg.batch, cfg.n_kv_heads, n_keep, dtype=torch.int32, device="cuda")
+    perm = torch.empty_like(idx)
+    ea.compress_layer_fp8(p, P.to_dev(lay["q_win"]), w, lay["q_pos0"], P.to_dev(lay["inv_freq"]), lay["t_next"],
+                          k8d, v8d, torch.from_numpy(ks).cuda(), torch.from_numpy(vs).cuda(), n, n, n_keep,
+                          order_free, sc, idx, perm, ws)
+    torch.cuda.synchronize()
+    ref = O.compress_layer(widen(lay["q_win"]), kd, vd, lay["q_pos0"], lay["inv_freq"], lay["t_next"], n_keep,
+                           T=cfg.horizon_T, epsilon=0.02, k_store=k8, v_store=v8)
+    gi = idx.cpu().numpy()
+    P.check_scores(sc.cpu().numpy(), ref["scores"], 2e-3)
+    P.check_idx_vs_oracle_scores(gi, ref["scores"], n_keep, 2e-3)
+    P.check_idx_exact_given_scores(gi, sc.cpu().numpy(), n_keep)
+    ka, va = k8d.cpu().numpy(), v8d.cpu().numpy()
+    if order_free:
+        for b in range(cfg.batch):
+            for h in range(cfg.n_kv_heads):
+                rperm = X.unordered_perm(gi[b, h], n_keep)
+                assert np.array_equal(perm.cpu().numpy()[b, h], rperm)
+                assert np.array_equal(ka[b, h, :n_keep], k8[b, h][rperm]) and np.array_equal(va[b, h, :n_keep], v8[b, h][rperm])
+        assert np.array_equal(ka[:, :, n_keep:], k8[:, :, n_keep:])
+    else:
+        P.check_compaction(ka, va, k8, v8, gi, n_keep)
+
+
+def test_compact_moves_fp8_rows():
+    """ea_compact and ea_compact_unordered with p->dtype = EA_FP8_E4M3: rows of d bytes."""
+    import torch
+    from oracle import ea_extensions as X
+    r = np.random.default_rng(9)
+    for d in (128, 256):
+        B, H, n = 2, 3, 4000
+        k8 = r.integers(0, 256, (B, H, n, d), dtype=np.uint8)
+        v8 = r.integers(0, 256, (B, H, n, d), dtype=np.uint8)
+        keep = np.sort(r.choice(n, 1700, replace=False)).astype(np.int32)
+        idx = np.broadcast_to(keep, (B, H, len(keep))).copy()
+        p = ea.make_params(B, H, H, d, ea.EA_FP8_E4M3)
+        ws = P.workspace(p, n, 1)
+        kd, vd = torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda()
+        ea.compact(p, kd, vd, n, n, torch.from_numpy(idx).cuda(), len(keep), kd, vd, ws)
+        torch.cuda.synchronize()
+        P.check_compaction(kd.cpu().numpy(), vd.cpu().numpy(), k8, v8, idx, len(keep))
+        kd, vd = torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda()
+        ea.compact_unordered(p, kd, vd, n, n, torch.from_numpy(idx).cuda(), len(keep))
+        torch.cuda.synchronize()
+        rperm = X.unordered_perm(keep, len(keep))
+        assert np.array_equal(kd.cpu().numpy()[:, :, :len(keep)], k8[:, :, rperm])
+        assert np.array_equal(vd.cpu().numpy()[:, :, :len(keep)], v8[:, :, rperm])

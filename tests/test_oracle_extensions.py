@@ -194,3 +194,29 @@ def test_paged_rows_on_a_hand_made_pool_and_against_the_generator_scatter():
     assert kp.shape == (nb, 3, 32, 4) and len(set(tab.ravel().tolist())) == tab.size
     np.testing.assert_array_equal(X.paged_rows(kp, tab, 75), k)
     np.testing.assert_array_equal(X.paged_rows(vp, tab, 75), v)
+
+
+def test_fp8_e4m3_decode_against_the_format_and_a_library_conversion():
+    # codes written out from the format's definition
+    known = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0, 0x3C: 1.5, 0x40: 2.0,
+             0x7E: 448.0, 0xB8: -1.0, 0xFE: -448.0, 0x80: -0.0}
+    for code, val in known.items():
+        assert X.fp8_e4m3_decode(np.array([code], np.uint8))[0] == val, hex(code)
+    assert np.isnan(X.fp8_e4m3_decode(np.array([0x7F, 0xFF], np.uint8))).all()
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    got = X.fp8_e4m3_decode(codes)
+    assert np.array_equal(np.isnan(lib), np.isnan(got))
+    ok = ~np.isnan(lib)
+    assert np.array_equal(lib[ok], got[ok])
+    # the generator's quantiser (torch's rounding) lands on codes whose decoded value is the nearest one
+    from ea_inputs import quantize_fp8
+    x = np.random.default_rng(2).standard_normal((1, 2, 50, 8)) * 3
+    q, sc = quantize_fp8(x)
+    back = X.fp8_e4m3_decode(q) * sc.astype(np.float64)[:, :, None, None]
+    grid = np.sort(got[ok])
+    y = x / sc.astype(np.float64)[:, :, None, None]
+    nearest = np.abs(y[..., None] - grid).min(axis=-1)
+    # (the quantiser rounds the float32 image of y: allow that rounding on top of the grid distance)
+    assert np.all(np.abs(back / sc.astype(np.float64)[:, :, None, None] - y) <= nearest + 1e-6 * np.abs(y))
