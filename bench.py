@@ -64,6 +64,9 @@ def parse():
     ap.add_argument("--paged", type=int, default=0, metavar="BLOCK",
                     help="prefill shapes: keep the cache in block pools of BLOCK rows behind a shuffled block "
                          "table and time ea_compress_layer_paged (0 = contiguous tensors)")
+    ap.add_argument("--fp8", action="store_true",
+                    help="prefill shapes: store K and V as e4m3 bytes with per-head scales and time "
+                         "ea_compress_layer_fp8 (half the bytes per pair)")
     ap.add_argument("--ordered", action="store_true",
                     help="decode schedule: use the order-preserving compaction instead of the order-free one")
     return ap.parse_args()
@@ -224,9 +227,30 @@ def run_prefill(a, torch, ea, cfg):
         k, v = torch.empty_like(k0), torch.empty_like(v0)
         pg_of = lambda l, lb: ea.make_paged(table[l * B:(l + lb) * B], bs, nblk)
 
+    scales = None
+    if a.fp8:
+        def quant(t):          # [L, B, Hkv, n, d] bf16 -> e4m3 bytes + fp32 scale per (layer, sequence, head)
+            sc = (t.abs().amax(dim=(3, 4), keepdim=True).float() / (448.0 * 0.9)).clamp_min(1e-30)
+            out = torch.empty(t.shape, dtype=torch.float8_e4m3fn, device=dev)
+            for l in range(L):
+                out[l] = (t[l].float() / sc[l]).to(torch.float8_e4m3fn)
+            return out, sc.reshape(L, B, Hkv).contiguous()
+        k8, ksc = quant(k0)
+        v8, vsc = quant(v0)
+        del k0, v0, k, v
+        k0, v0 = k8, v8
+        k, v = torch.empty_like(k0), torch.empty_like(v0)
+        scales = (ksc, vsc)
+
     def restore():
         k.copy_(k0)
         v.copy_(v0)
+
+    def step_fp8():
+        for i, l in enumerate(range(0, L, LB)):
+            ea.compress_layer_fp8(p, q[l:l + LB], w, q_pos0, inv, t_next, k[l:l + LB], v[l:l + LB],
+                                  scales[0][l:l + LB], scales[1][l:l + LB], n, n, n_keep, 0, None, None, None,
+                                  wss[i % ns], stream=streams[i % ns])
 
     def step_paged():
         for i, l in enumerate(range(0, L, LB)):
@@ -236,6 +260,8 @@ def run_prefill(a, torch, ea, cfg):
     def step():
         if a.paged:
             return step_paged()
+        if a.fp8:
+            return step_fp8()
         # call i runs on stream i % ns with that stream's workspace; the caller synchronises the
         # device before and after a step
         for i, l in enumerate(range(0, L, LB)):
@@ -262,18 +288,21 @@ def run_prefill(a, torch, ea, cfg):
     ms_per_step = 1e3 * sum(times) / len(times)
     pairs = L * B * Hkv * n
     f = n_keep / n
-    bytes_per_pair = 2 * d * 2 * (1 + 2 * f)                     # K,V read once + kept rows read+written
+    bytes_per_pair = 2 * d * (1 if a.fp8 else 2) * (1 + 2 * f)    # K,V read once + kept rows read+written
     frac = lambda ms: pairs * bytes_per_pair / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
     layer_by_layer = None
-    if a.paged:
+    if a.paged or a.fp8:
         out = {"metric": "KV pairs scored+compacted/sec", "value": round(pairs / (ms_per_step * 1e-3) / 1e9, 4),
                "unit": "G pairs/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
                "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-               "dtype": "bf16", "data": "synthetic",
-               "config": {"workload": "%s, paged: %d layers x %d KV heads x %d tokens x d%d in pools of %d-row blocks "
-                                      "behind a shuffled block table, ratio %.2f, %d layer(s) per call, %d streams" %
-                                      (cfg.name, L, Hkv * B, n, d, a.paged, a.ratio, LB, ns),
+               "dtype": "fp8 cache, fp16 matrix-core operands" if a.fp8 else "bf16", "data": "synthetic",
+               "config": {"workload": ("%s, paged: %d layers x %d KV heads x %d tokens x d%d in pools of %d-row blocks "
+                                       "behind a shuffled block table, ratio %.2f, %d layer(s) per call, %d streams" %
+                                       (cfg.name, L, Hkv * B, n, d, a.paged, a.ratio, LB, ns)) if a.paged else
+                                      ("%s, K and V stored as e4m3 bytes with per-head scales: %d layers x %d KV heads x "
+                                       "%d tokens x d%d, ratio %.2f, %d layer(s) per call, %d streams" %
+                                       (cfg.name, L, Hkv * B, n, d, a.ratio, LB, ns)),
                           "pairs_per_step": pairs, "bytes_per_pair": bytes_per_pair},
                "path_hbm_frac": round(frac(ms_per_step), 4)}
         return out
