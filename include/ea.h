@@ -77,7 +77,10 @@ size_t ea_workspace_bytes(const ea_params* p, int64_t n, int64_t window);
 /* Eq. 5-6: statistics of the position-averaged query distribution.
  *   u_s = R(q_pos0+s)^T q_s (skipped when q_is_rotated = 0); m, S = mean / covariance of
  *   the u_s; R-bar = average of R(t_next .. t_next+T-1); mu = R-bar m; sigma = R-bar S R-bar^T.
- * inv_freq: DEVICE pointer, fp64 [d/2].  Needs 1 + cov_ddof <= window <= 4096. */
+ * inv_freq: DEVICE pointer, fp64 [d/2].  Needs 1 + cov_ddof <= window <= 4096.
+ * bf16 windows: the covariance sums run on the fp16 matrix cores over samples scaled by a power
+ * of two taken from the head's first 64 (32 at d = 256) samples; a later sample more than 2000
+ * times larger than all of those in some channel overflows to non-finite statistics. */
 ea_status ea_query_stats(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
                          const double* inv_freq, int64_t t_next, float* mu, float* sigma,
                          void* ws, size_t ws_bytes, void* stream);

@@ -348,6 +348,296 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats(const void* _
 }
 
 // ---------------------------------------------------------------------------------------
+// The same statistics for bf16 windows with the outer products on the fp16 matrix cores.
+//
+// fp32 matrix-core instructions run at the rate of the vector units (and do not overlap with
+// vector work), which made the kernel above the largest stage of a decode-time pass (512-sample
+// windows).  Here every shifted sample x = u~ - u~_0 is scaled by a power of two s and split into
+// two fp16 numbers, x s = hi + lo (hi = x s rounded toward zero to fp16, lo = the remainder
+// rounded to fp16: 21 significant bits together), and
+//     sum_s x x^T  =  (1/s^2) sum_s (hi hi^T + hi lo^T + lo hi^T)  + O(2^-21)
+// runs as three v_mfma_f32_32x32x16_f16 per tile and 16 samples (96 cycles instead of 512), with
+// fp32 accumulation.  The samples are the contraction index, so the chunk is staged transposed:
+// two planes [channel][chunk of 64 or 32 samples] of fp16 with a row pitch of 8 more (conflict-free
+// 16-byte reads).
+// s is taken from the largest |x| of the head's first chunk (that chunk lands in [16, 32)), which
+// leaves a factor 2048 of headroom for later samples before fp16 overflows (an overflow shows as
+// non-finite statistics, and then as the NaN-score bit of the status word).  Mean, column sums,
+// the shift and the final algebra are those of k_stats, in fp32.
+typedef _Float16 stats_half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 stats_half2 __attribute__((ext_vector_type(2)));
+// samples per staged chunk: 64, and 32 at d = 256 (registers: a thread keeps its share of the next
+// chunk's queries and table rows in flight during the matrix-core loop)
+constexpr int stats_split_chunk(int D) { return D >= 256 ? 32 : 64; }
+
+template <int D, int LAYOUT>
+__global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats_split(const void* __restrict__ q_win, int w,
+                                                                         int ddof,
+                                                                         const float2* __restrict__ tab,
+                                                                         float* __restrict__ mu,
+                                                                         float* __restrict__ sigma) {
+  constexpr int HALF = D / 2, G8 = HALF / 8, layout = LAYOUT;   // the channel pairing is a compile-time constant:
+                                                                // every LDS address below is a base plus an immediate
+  constexpr int WC = stats_split_chunk(D);            // samples per chunk
+  constexpr int ITEMS = WC * G8 / 256;                // consecutive samples per thread and chunk
+  constexpr int P = WC + 8;                           // halves per channel row of a plane
+  typedef StatsTiling<D> TL;
+  constexpr int NCT = TL::NCT, TPW = TL::SLOTS;
+  static_assert(ITEMS >= 1 && 256 % G8 == 0, "one channel group per thread");
+  static_assert(TL::SHARED * 4 * 16 * 64 * 4 <= 2 * D * P * 2, "partial tiles fit in the planes");
+  extern __shared__ __align__(16) float s_dyn[];
+  _Float16* s_hi = reinterpret_cast<_Float16*>(s_dyn);            // [D][P]
+  _Float16* s_lo = s_hi + D * P;                                   // [D][P]
+  float* s_part = reinterpret_cast<float*>(s_lo + D * P);          // [4][D] column sums per wavefront
+  float* s_shift = s_part + 4 * D;                                 // [D] u~_0
+  float* s_xbar = s_shift + D;                                     // [D]
+  float* s_max = s_xbar + D;                                       // [4]
+  const int head = blockIdx.x, part = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const size_t qbase = (size_t)head * w * D;
+  const int nchunks = (w + WC - 1) / WC;
+  const int g = tid % G8, sl_t = ITEMS * (tid / G8);   // this thread's channel group and first sample of a chunk
+
+  StatsRaw<true> raw[ITEMS];
+  auto load_chunk = [&](int ch) __attribute__((always_inline)) {
+    const int s0 = ch * WC, ns = min(WC, w - s0);
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+      const int sl = min(sl_t + it, ns - 1);            // no load under a condition: past the end, the last sample again
+      stats_fetch_item<D, true>(q_win, qbase + (size_t)(s0 + sl) * D, g, layout, tab + (size_t)(s0 + sl) * HALF, raw[it]);
+    }
+  };
+  load_chunk(0);
+  if (tid < G8) {
+    float qa[8], qb[8];
+    float2 tb[8];
+    StatsRaw<true> raw0;
+    stats_fetch_item<D, true>(q_win, qbase, g, layout, tab, raw0);
+    stats_unpack_item<true>(raw0, layout, qa, qb, tb);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      s_shift[stats_ja<D>(layout, g, e)] = tb[e].x * qa[e] - tb[e].y * qb[e];
+      s_shift[stats_jb<D>(layout, g, e)] = tb[e].y * qa[e] + tb[e].x * qb[e];
+    }
+  }
+  __syncthreads();
+  float suma[8], sumb[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { suma[e] = 0.f; sumb[e] = 0.f; }
+
+  const int r32 = lane & 31, kg = lane >> 5;
+  int t_rb[TPW], t_ct[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    const int local = t < TL::WHOLE ? wave + 4 * t : 4 * TL::WHOLE + (t - TL::WHOLE);
+    int idx = part * TL::TP + local, rb = 0;
+    const bool ok = local < TL::TP && idx < TL::NT;
+    if (!ok) idx = 0;
+#pragma unroll
+    for (int r = 0; r < NCT; ++r)
+      if (idx >= NCT - rb && rb == r) { idx -= NCT - rb; ++rb; }
+    t_rb[t] = ok ? rb : -1;
+    t_ct[t] = rb + idx;
+  }
+  floatx16_t acc[TPW];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+  // x = u~ - u~_0 of item `it` of the chunk in flight (zeros past the chunk's end): [0, 8) the first,
+  // [8, 16) the second channels of the group's pairs
+  auto item_x = [&](int it, int ns, float (&x)[16]) __attribute__((always_inline)) {
+    float qa[8], qb[8];
+    float2 tb[8];
+    stats_unpack_item<true>(raw[it], layout, qa, qb, tb);
+    const bool ok = sl_t + it < ns;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      x[e] = ok ? tb[e].x * qa[e] - tb[e].y * qb[e] - s_shift[stats_ja<D>(layout, g, e)] : 0.f;
+      x[8 + e] = ok ? tb[e].y * qa[e] + tb[e].x * qb[e] - s_shift[stats_jb<D>(layout, g, e)] : 0.f;
+    }
+  };
+
+  float scale = 1.0f;
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int ns = min(WC, w - ch * WC);
+    // ---- this thread's samples of the chunk, then at once the requests for the next chunk: they
+    //      travel during the conversion, the barriers and the matrix-core loop below
+    float xs[ITEMS][16];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) item_x(it, ns, xs[it]);
+    if (ch + 1 < nchunks) load_chunk(ch + 1);
+    if (ch == 0) {
+      // the head's scale: a power of two that puts the first chunk's largest |x| into [16, 32)
+      float amax = 0.f;
+#pragma unroll
+      for (int it = 0; it < ITEMS; ++it)
+#pragma unroll
+        for (int c16 = 0; c16 < 16; ++c16) amax = fmaxf(amax, fabsf(xs[it][c16]));
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+      if (lane == 0) s_max[wave] = amax;
+      __syncthreads();
+      const float m = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+      if (m > 0.f && m < INFINITY) {
+        int ex;
+        frexpf(m, &ex);                               // m = f 2^ex, f in [0.5, 1)
+        scale = ldexpf(1.0f, max(-100, min(100, 5 - ex)));
+      }
+    } else {
+      __syncthreads();                                // the previous chunk has been consumed
+    }
+    // ---- fp16 (hi, lo) of x * scale into the transposed planes, column sums on the way
+#pragma unroll
+    for (int it = 0; it < ITEMS; it += 2) {
+#pragma unroll
+      for (int c16 = 0; c16 < 16; ++c16) {
+        const int e = c16 & 7;
+        const int c = c16 < 8 ? stats_ja<D>(layout, g, e) : stats_jb<D>(layout, g, e);
+        const float x0 = xs[it][c16];
+        const float y0 = x0 * scale;
+        if constexpr (ITEMS >= 2) {
+          const float x1 = xs[it + 1][c16];
+          if (c16 < 8) suma[e] += x0 + x1; else sumb[e] += x0 + x1;
+          const float y1 = x1 * scale;
+          const stats_half2 h = __builtin_bit_cast(stats_half2, __builtin_amdgcn_cvt_pkrtz(y0, y1));
+          const stats_half2 l = {(_Float16)(y0 - (float)h[0]), (_Float16)(y1 - (float)h[1])};
+          *reinterpret_cast<stats_half2*>(s_hi + c * P + sl_t + it) = h;
+          *reinterpret_cast<stats_half2*>(s_lo + c * P + sl_t + it) = l;
+        } else {
+          if (c16 < 8) suma[e] += x0; else sumb[e] += x0;
+          const stats_half2 h = __builtin_bit_cast(stats_half2, __builtin_amdgcn_cvt_pkrtz(y0, 0.f));
+          s_hi[c * P + sl_t] = h[0];
+          s_lo[c * P + sl_t] = (_Float16)(y0 - (float)h[0]);
+        }
+      }
+    }
+    __syncthreads();
+    // ---- three matrix-core instructions per tile and 16 samples
+    const int nks = (ns + 15) / 16;
+#pragma unroll 1
+    for (int ks = 0; ks < nks; ++ks) {
+#pragma unroll
+      for (int t = 0; t < TPW; ++t) {
+        if (t_rb[t] >= 0 && (t < TL::WHOLE || ((ch * (WC / 16) + ks) & 3) == wave)) {
+          const int ra = (t_rb[t] * 32 + r32) * P + ks * 16 + kg * 8;
+          const int rbw = (t_ct[t] * 32 + r32) * P + ks * 16 + kg * 8;
+          const stats_half8 ah = *reinterpret_cast<const stats_half8*>(s_hi + ra);
+          const stats_half8 al = *reinterpret_cast<const stats_half8*>(s_lo + ra);
+          const stats_half8 bh = *reinterpret_cast<const stats_half8*>(s_hi + rbw);
+          const stats_half8 bl = *reinterpret_cast<const stats_half8*>(s_lo + rbw);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh, acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl, acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh, acc[t], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (TL::SHARED > 0) {
+    // the four partial tiles of every shared tile, added in wavefront order by wavefront 0
+    float* s_u = s_dyn;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < TL::SHARED; ++r)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_u[((r * 4 + wave) * 16 + v) * 64 + lane] = acc[TL::WHOLE + r][v];
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int r = 0; r < TL::SHARED; ++r)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float* pp = s_u + (r * 4 * 16 + v) * 64 + lane;
+          acc[TL::WHOLE + r][v] = (pp[0] + pp[16 * 64]) + (pp[2 * 16 * 64] + pp[3 * 16 * 64]);
+        }
+    }
+  }
+
+  // column sums: lanes that share a channel group (stride G8) first, then the four wavefronts
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+#pragma unroll
+    for (int o = G8; o < 64; o <<= 1) {
+      suma[e] += __shfl_xor(suma[e], o);
+      sumb[e] += __shfl_xor(sumb[e], o);
+    }
+  }
+  if (lane < G8) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      s_part[wave * D + stats_ja<D>(layout, g, e)] = suma[e];
+      s_part[wave * D + stats_jb<D>(layout, g, e)] = sumb[e];
+    }
+  }
+  __syncthreads();
+  const float invw = 1.0f / (float)w;
+  for (int c = tid; c < D; c += 256) {
+    const float xb = ((s_part[c] + s_part[D + c]) + (s_part[2 * D + c] + s_part[3 * D + c])) * invw;
+    s_xbar[c] = xb;
+    if (part == 0) mu[(size_t)head * D + c] = s_shift[c] + xb;
+  }
+  __syncthreads();
+  // In the matrix-core product a lane's B operand is column r32 and its A rows come back as
+  // accumulator register v = row 8 (v / 4) + 4 kg + v % 4: the tile's entry (row, column r32).
+  const float fw = (float)w, inv = 1.0f / (float)(w - ddof), unscale = 1.0f / (scale * scale);
+  // A tile above the diagonal is also stored transposed.  Straight from the accumulators that is
+  // 64 separate 4-byte writes per instruction (a lane holds one column).  At d = 256 (28 of 36 tiles
+  // are mirrored, 64 MB of Sigma per launch of the four-sequence shape) the tile takes a trip
+  // through the wavefront's own patch of LDS (the planes are free by now) and leaves as rows; at
+  // d <= 128 that costs the registers that keep three workgroups on a CU without scratch memory,
+  // and the direct stores are the faster ones (5.6 against 10.4 us per layer at the decode shape).
+  constexpr bool kViaLds = D >= 256;
+  if constexpr (!kViaLds) {
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+      if (t_rb[t] >= 0 && (t < TL::WHOLE || wave == 0)) {
+        const int i0 = t_rb[t] * 32, j = t_ct[t] * 32 + r32;
+        const bool mirror = t_rb[t] != t_ct[t];
+        const float xj = s_xbar[j];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = i0 + 8 * (v / 4) + 4 * kg + v % 4;
+          const float val = (acc[t][v] * unscale - fw * s_xbar[i] * xj) * inv;
+          sigma[((size_t)head * D + i) * D + j] = val;
+          if (mirror) sigma[((size_t)head * D + j) * D + i] = val;
+        }
+      }
+    }
+  } else {
+    float* s_tr = s_dyn + wave * (32 * 33);
+    static_assert(4 * 32 * 33 * 4 <= 2 * D * P * 2, "transposition patches fit in the planes");
+    __syncthreads();                 // every wavefront is done with the planes (and the partial tiles)
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+      if (t_rb[t] >= 0 && (t < TL::WHOLE || wave == 0)) {
+        const int i0 = t_rb[t] * 32, j0 = t_ct[t] * 32, j = j0 + r32;
+        const bool mirror = t_rb[t] != t_ct[t];
+        const float xj = s_xbar[j];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int il = 8 * (v / 4) + 4 * kg + v % 4;
+          const float val = (acc[t][v] * unscale - fw * s_xbar[i0 + il] * xj) * inv;
+          sigma[((size_t)head * D + i0 + il) * D + j] = val;
+          if (mirror) s_tr[r32 * 33 + il] = val;         // [column][row]
+        }
+        if (mirror) {
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int jl = 2 * v + kg;                    // column of the tile = row of the transposed one
+            sigma[((size_t)head * D + j0 + jl) * D + i0 + r32] = s_tr[jl * 33 + r32];
+          }
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Matrix-core operands for the score kernel, one workgroup per (unit, pass).
 //
 // The quadratic form k^T Sigma k is evaluated as sum_j (sum_c k_c M[c][j]) k_j where M folds
@@ -507,15 +797,35 @@ static hipError_t launch_stats_one(const Dims& d, const void* q_win, int w, cons
   return hipGetLastError();
 }
 
+template <int D, int LAYOUT>
+static hipError_t launch_stats_split_one(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
+                                         float* sigma, hipStream_t st) {
+  auto kern = k_stats_split<D, LAYOUT>;
+  const size_t lds = (size_t)2 * D * (stats_split_chunk(D) + 8) * sizeof(_Float16) + (size_t)(6 * D + 4) * sizeof(float);
+  static LdsOptIn opt;
+  hipError_t e = opt.ensure(reinterpret_cast<const void*>(kern), lds);
+  if (e != hipSuccess) return e;
+  dim3 grid(d.qheads(), StatsTiling<D>::PARTS);
+  kern<<<grid, 256, lds, st>>>(q_win, w, d.ddof, tab, mu, sigma);
+  return hipGetLastError();
+}
+template <int D>
+static hipError_t launch_stats_split(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
+                                     float* sigma, hipStream_t st) {
+  return d.rope_layout ? launch_stats_split_one<D, 1>(d, q_win, w, tab, mu, sigma, st)
+                       : launch_stats_split_one<D, 0>(d, q_win, w, tab, mu, sigma, st);
+}
+
 hipError_t launch_stats(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
                         float* sigma, hipStream_t st) {
   const bool bf = d.dtype == EA_BF16;
-  if (d.D == 64) return bf ? launch_stats_one<64, true>(d, q_win, w, tab, mu, sigma, st)
-                           : launch_stats_one<64, false>(d, q_win, w, tab, mu, sigma, st);
-  if (d.D == 128) return bf ? launch_stats_one<128, true>(d, q_win, w, tab, mu, sigma, st)
-                            : launch_stats_one<128, false>(d, q_win, w, tab, mu, sigma, st);
-  return bf ? launch_stats_one<256, true>(d, q_win, w, tab, mu, sigma, st)
-            : launch_stats_one<256, false>(d, q_win, w, tab, mu, sigma, st);
+  // bf16 windows: outer products on the fp16 matrix cores (split operands); fp32 windows: fp32 ones
+  if (bf && d.D == 64) return launch_stats_split<64>(d, q_win, w, tab, mu, sigma, st);
+  if (bf && d.D == 128) return launch_stats_split<128>(d, q_win, w, tab, mu, sigma, st);
+  if (bf) return launch_stats_split<256>(d, q_win, w, tab, mu, sigma, st);
+  if (d.D == 64) return launch_stats_one<64, false>(d, q_win, w, tab, mu, sigma, st);
+  if (d.D == 128) return launch_stats_one<128, false>(d, q_win, w, tab, mu, sigma, st);
+  return launch_stats_one<256, false>(d, q_win, w, tab, mu, sigma, st);
 }
 
 hipError_t launch_prep_frags(const Dims& d, const ScorePlan& sp, const float* mu,

@@ -79,6 +79,20 @@ def test_query_stats_variants(variant):
     P.check_stats(mu, sg, rmu, rsg)
 
 
+@pytest.mark.parametrize("factor", [2.0 ** 10, 2.0 ** -10, 2.0 ** 40])
+def test_query_stats_bf16_is_scale_free(factor):
+    """The bf16 path splits the shifted samples into fp16 halves after scaling them by a power of
+    two taken from the data: windows a thousand times larger or smaller than the generator's (and
+    far outside fp16 range) give the same relative accuracy."""
+    from ea_inputs import bf16_bits_from_f64
+    cfg = CONFIGS["c5"].with_(n_q_heads=5, n_kv_heads=1)
+    lay = make_layer(cfg, n=700, window=300, pos0=12345)
+    lay = dict(lay, q_win=bf16_bits_from_f64(widen(lay["q_win"]) * factor))     # exact: a power of two
+    mu, sg = P.run_query_stats(cfg, lay)
+    rmu, rsg = _oracle_stats(cfg, lay)
+    P.check_stats(mu, sg, rmu, rsg)
+
+
 # ------------------------------------------------------------------------------- ea_score
 @pytest.mark.parametrize("eps", [0.02, 0.0])
 @pytest.mark.parametrize("name", list(MINI))
