@@ -205,10 +205,11 @@ def test_score_c2_full_size():
 
 # ------------------------------------------------------------------------------ ea_select
 @pytest.mark.parametrize("n,n_keep", [(1, 1), (1, 0), (5, 3), (4096, 2048), (4097, 1), (5000, 4999),
-                                      (5000, 5000), (20000, 7), (32768, 30000), (32769, 1), (32769, 32768),
+                                      (5000, 5000), (16384, 9000), (16385, 1), (16385, 16384), (20000, 7),
+                                      (32768, 30000), (32769, 1), (32769, 32768),
                                       (70000, 35000), (70001, 69999)])
 def test_select_exact(n, n_keep):
-    # heads of up to 32768 scores are selected by one workgroup out of LDS, longer ones by the
+    # heads of up to 16384 scores are selected by one workgroup out of LDS, longer ones by the
     # multi-launch histogram path: sizes on both sides of the switch
     cfg = CONFIGS["c2"].with_(batch=2, n_kv_heads=3, n_q_heads=3)
     r = np.random.default_rng(n * 7 + n_keep)
