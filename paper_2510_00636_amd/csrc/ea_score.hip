@@ -359,9 +359,10 @@ hipError_t launch_wnorm(const void* logits, int logits_f64, size_t count, int D,
   return hipGetLastError();
 }
 
-constexpr int kLseInlineMax = 1024;   // more partials per head than this: reduce them in k_lse first
+constexpr int kLseInlineMax = 256;    // more partials per head than this: reduce them in k_lse first
                                       // (one short launch; every finalize workgroup then reads G numbers
-                                      // instead of re-reducing thousands: 12.0 -> 8.4 us per layer at 4096)
+                                      // instead of re-reducing the list: at 1024 partials per head, one
+                                      // 131072-key layer per call, pass B takes 14.8 instead of 18.1 us)
 
 hipError_t launch_finalize(const Dims& d, int64_t n, const void* logits, int logits_f64,
                            const float* vnorm, const void* part, int npart, void* lse, float* scores,
