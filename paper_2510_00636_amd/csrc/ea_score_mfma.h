@@ -445,6 +445,10 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     //   * the squared norm of V chunk j is formed at step j;
     //   * the 2*NL global loads of the next tile are spread over the steps after the extra
     //     tile, one at a time, so they never queue up in front of the memory pipeline.
+    // The matrix-core phase runs at a raised wave priority: when the other wave of the SIMD is in
+    // its staging or store phase, this wave's instructions are issued first and the matrix pipeline
+    // stays fed (4 % on the kernel; the level, 1 to 3, makes no difference).
+    __builtin_amdgcn_s_setprio(1);
     float lin[GH], partial[GH], vsq = 0.f;
     static_for<GH>([&](auto g_) { partial[decltype(g_)::value] = 0.f; lin[decltype(g_)::value] = 0.f; });
     {
@@ -542,6 +546,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
         __builtin_amdgcn_sched_barrier(0);
       });
     }
+    __builtin_amdgcn_s_setprio(0);
     // The softmax over keys (Eq. 8) is not this kernel's business: the (max, sum exp) partials are
     // taken from the stored logits per fixed block of keys by a pass of their own (k_lse_part), so
     // they do not depend on which wave scored which tile.
