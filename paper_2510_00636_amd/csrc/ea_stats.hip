@@ -381,6 +381,15 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats_split(const v
   constexpr int WC = stats_split_chunk(D);            // samples per chunk
   constexpr int ITEMS = WC * G8 / 256;                // consecutive samples per thread and chunk
   constexpr int P = WC + 8;                           // halves per channel row of a plane
+  // Rows eight channels apart start 0 or 32 banks apart whatever the (16-byte aligned) pitch, and
+  // those are the rows the lanes of one staging write go to (one channel of every group): the
+  // 16-byte column blocks of a row are therefore XOR-swizzled by the row's channel group, which
+  // spreads the groups over the blocks (writes conflict-free at d = 128, two-way at d = 256) and
+  // leaves the 16 lanes of a matrix-operand read (two groups of equal swizzle) in one block.
+  constexpr int NB = WC / 8;                          // column blocks per row
+  constexpr int BW = G8 >= 16 ? 1 : 16 / G8;          // blocks one wave-wide staging write spans
+  auto swz_of_group = [](int gg) { return ITEMS >= 2 ? ((gg >> 1) * BW) % NB : 0; };
+  auto group_of_channel = [](int c) { return LAYOUT ? c / 16 : (c % HALF) / 8; };
   typedef StatsTiling<D> TL;
   constexpr int NCT = TL::NCT, TPW = TL::SLOTS;
   static_assert(ITEMS >= 1 && 256 % G8 == 0, "one channel group per thread");
@@ -503,8 +512,9 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats_split(const v
           const float y1 = x1 * scale;
           const stats_half2 h = __builtin_bit_cast(stats_half2, __builtin_amdgcn_cvt_pkrtz(y0, y1));
           const stats_half2 l = {(_Float16)(y0 - (float)h[0]), (_Float16)(y1 - (float)h[1])};
-          *reinterpret_cast<stats_half2*>(s_hi + c * P + sl_t + it) = h;
-          *reinterpret_cast<stats_half2*>(s_lo + c * P + sl_t + it) = l;
+          const int col = ((((sl_t + it) >> 3) ^ swz_of_group(g)) << 3) + ((sl_t + it) & 7);
+          *reinterpret_cast<stats_half2*>(s_hi + c * P + col) = h;
+          *reinterpret_cast<stats_half2*>(s_lo + c * P + col) = l;
         } else {
           if (c16 < 8) suma[e] += x0; else sumb[e] += x0;
           const stats_half2 h = __builtin_bit_cast(stats_half2, __builtin_amdgcn_cvt_pkrtz(y0, 0.f));
@@ -521,8 +531,9 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats_split(const v
 #pragma unroll
       for (int t = 0; t < TPW; ++t) {
         if (t_rb[t] >= 0 && (t < TL::WHOLE || ((ch * (WC / 16) + ks) & 3) == wave)) {
-          const int ra = (t_rb[t] * 32 + r32) * P + ks * 16 + kg * 8;
-          const int rbw = (t_ct[t] * 32 + r32) * P + ks * 16 + kg * 8;
+          const int ca = t_rb[t] * 32 + r32, cb = t_ct[t] * 32 + r32;
+          const int ra = ca * P + (((ks * 2 + kg) ^ swz_of_group(group_of_channel(ca))) << 3);
+          const int rbw = cb * P + (((ks * 2 + kg) ^ swz_of_group(group_of_channel(cb))) << 3);
           const stats_half8 ah = *reinterpret_cast<const stats_half8*>(s_hi + ra);
           const stats_half8 al = *reinterpret_cast<const stats_half8*>(s_lo + ra);
           const stats_half8 bh = *reinterpret_cast<const stats_half8*>(s_hi + rbw);
