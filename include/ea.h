@@ -223,7 +223,7 @@ ea_status ea_compress_layer_unordered(const ea_params* p, const void* q_win, int
  * [0, num_blocks) are clamped into the pool (wrong results, no access outside it).
  * order_free != 0 selects the order-free compaction (see ea_compact_unordered); perm_out is only
  * written then (nullable).  EA_ERR_UNSUPPORTED for fp32 caches and for block sizes that are not a
- * power of two in [32, 65536]. */
+ * power of two in [16, 65536]. */
 typedef struct {
   const int32_t* block_table; /* DEVICE [B, max_blocks] int32                                */
   int32_t block_size;         /* rows per block                                              */

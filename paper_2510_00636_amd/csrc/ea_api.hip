@@ -306,7 +306,7 @@ ea_status ea_compact(const ea_params* p, const void* k, const void* v, int64_t n
 static ea_status check_paged(const Dims& d, const ea_paged* pg, int64_t n, PageMap* pm) {
   if (!pg || !pg->block_table || ((uintptr_t)pg->block_table & 3u)) return EA_ERR_INVALID_ARG;
   const int64_t bs = pg->block_size;
-  if (bs < 32 || bs > 65536 || (bs & (bs - 1)) != 0) return EA_ERR_UNSUPPORTED;
+  if (bs < 16 || bs > 65536 || (bs & (bs - 1)) != 0) return EA_ERR_UNSUPPORTED;
   if (pg->max_blocks < 1 || pg->num_blocks < 1 || pg->num_blocks > ((int64_t)1 << 31)) return EA_ERR_INVALID_ARG;
   if ((int64_t)pg->max_blocks * bs < n) return EA_ERR_INVALID_ARG;
   if (d.dtype != EA_BF16) return EA_ERR_UNSUPPORTED;

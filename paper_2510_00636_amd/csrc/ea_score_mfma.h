@@ -193,9 +193,9 @@ constexpr int load_slot(int i) { return NX + (i * (NS - NX)) / (2 * NL); }
 // Ragged tail: the last tile of a head is moved back to start at n - 32, so it overlaps its
 // predecessor instead of running past the tensor; the keys it shares with the predecessor are
 // recomputed and masked out of the stores.  The CLAMP instance clamps every row index to n - 1
-// instead (per-lane row offsets, a few more vector instructions per tile): it serves heads
-// shorter than one tile (n < 32) and paged caches, where a tile must not leave its block (tiles
-// then start at multiples of 32 and the block size is a multiple of 32).
+// instead (per-lane piece addresses, a few more vector instructions per tile): it serves heads
+// shorter than one tile (n < 32) and paged caches (tiles then start at multiples of 32, so a tile
+// lies inside one block, or in two for blocks of 16 rows).
 //
 // FP8 instances read caches stored as OCP e4m3 bytes with one fp32 scale per (sequence, KV head):
 // a 16-byte chunk then holds 16 channels (two k-steps of a lane), rows are half as long, the
@@ -296,16 +296,23 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   auto tile_key = [&](int ticket) -> long long { return (long long)(ntiles - 1 - ticket) * 32; };
   const u32x4* kbase = a.k + (size_t)unit * a.n_cap * CPR;
   const u32x4* vbase = a.v + (size_t)unit * a.n_cap * CPR;
-  // CLAMP: row offset (in 16-byte pieces) of this lane's piece of wave-wide load j of the tile at
-  // key0, rows past the end of the head clamped to its last row; first row of the tile inside
-  // the tensor or, for paged caches, inside the pool (a wave-uniform table lookup)
-  auto lane_off = [&](long long k0, int j) -> int {
-    const int lim = (int)min((long long)31, a.n - 1 - k0);
-    return min(j * RPL + lrow, lim) * CPR + lch;
+  // CLAMP: where the tile at key0 lies -- the tensor's (or, for paged caches, the pool's) row that
+  // holds tile row 0 and the one that holds tile row 16 (blocks of 16 rows: a tile spans two of
+  // them; the lookups are wave-uniform) -- and the 16-byte piece this lane fetches with wave-wide
+  // load j, rows past the end of the head clamped to its last row.
+  auto tile_rows = [&](long long k0, size_t& r0, size_t& r1) {
+    if (a.pm.table) {
+      r0 = paged_row(a.pm, unit, (int)k0);
+      r1 = (a.pm.sh < 5 && k0 + 16 < a.n) ? paged_row(a.pm, unit, (int)k0 + 16) : r0 + 16;
+    } else {
+      r0 = (size_t)unit * a.n_cap + k0;
+      r1 = r0 + 16;
+    }
   };
-  auto tile_row0 = [&](long long k0) -> size_t {
-    if (a.pm.table) return paged_row(a.pm, unit, (int)k0);
-    return (size_t)unit * a.n_cap + k0;
+  auto lane_piece = [&](long long k0, int j, size_t r0, size_t r1) -> size_t {
+    const int lim = (int)min((long long)31, a.n - 1 - k0);
+    const int re = min(j * RPL + lrow, lim);
+    return (re < 16 ? r0 + re : r1 + (re - 16)) * CPR + lch;
   };
 
   // One 32-key tile = NL wave-wide 16-byte loads per tensor, addressed as (uniform tile base)
@@ -335,11 +342,12 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
         for (int j = 0; j < NL; ++j) vraw[j] = __builtin_nontemporal_load(&vp[j * 64 + lane]);
       }
     } else {
-      const size_t r0 = tile_row0(key0) * CPR;
+      size_t r0, r1;
+      tile_rows(key0, r0, r1);
 #pragma unroll
       for (int j = 0; j < NL; ++j) {
-        kraw[j] = a.k[r0 + lane_off(key0, j)];
-        if (do_v) vraw[j] = a.v[r0 + lane_off(key0, j)];
+        kraw[j] = a.k[lane_piece(key0, j, r0, r1)];
+        if (do_v) vraw[j] = a.v[lane_piece(key0, j, r0, r1)];
       }
     }
   }
@@ -424,13 +432,14 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
     const u32x4* vp_n = (has_next && do_v) ? vbase + tile_base(nkey0) * CPR : vbase;
     const int kl = has_next ? lane : 0, vl = (has_next && do_v) ? lane : 0;
     const int kj = has_next ? 64 : 0, vj = (has_next && do_v) ? 64 : 0;
-    int noff[CLAMP ? NL : 1];           // CLAMP: per-lane piece offsets of the next tile's loads
+    size_t noff[CLAMP ? NL : 1];        // CLAMP: this lane's pieces of the next tile's loads
     if constexpr (CLAMP) {
-      const size_t r0 = has_next ? tile_row0(nkey0) * CPR : (size_t)0;
-      kp_n = has_next ? a.k + r0 : kbase;
-      vp_n = (has_next && do_v) ? a.v + r0 : vbase;
+      size_t r0 = 0, r1 = 0;
+      if (has_next) tile_rows(nkey0, r0, r1);
+      kp_n = a.k;                       // (without a next tile: piece 0 of the tensor, as above)
+      vp_n = a.v;
 #pragma unroll
-      for (int j = 0; j < NL; ++j) noff[j] = has_next ? lane_off(nkey0, j) : 0;
+      for (int j = 0; j < NL; ++j) noff[j] = has_next ? lane_piece(nkey0, j, r0, r1) : (size_t)0;
     }
 
     // ---- matrix-core phase: NS = 2*NKS + GH*NF steps, one LDS fragment and one MFMA each.
@@ -533,7 +542,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
           if constexpr (f < NS && load_slot<NX, NS, NL>(i) == f) {
             if constexpr (CLAMP) {
               if constexpr (i < NL) kraw[i] = kNtK ? __builtin_nontemporal_load(&kp_n[noff[i]]) : kp_n[noff[i]];
-              else vraw[i - NL] = __builtin_nontemporal_load(&vp_n[do_v ? noff[i - NL] : 0]);
+              else vraw[i - NL] = __builtin_nontemporal_load(&vp_n[do_v ? noff[i - NL] : (size_t)0]);
             } else {
               if constexpr (i < NL) kraw[i] = kNtK ? __builtin_nontemporal_load(&kp_n[i * kj + kl]) : kp_n[i * kj + kl];
               else vraw[i - NL] = __builtin_nontemporal_load(&vp_n[(i - NL) * vj + vl]);

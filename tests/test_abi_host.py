@@ -123,7 +123,7 @@ def test_bench_refuses_more_than_one_gpu():
 
 
 def test_paged_arguments_are_checked_on_the_host(lib):
-    """Block sizes that are not a power of two in [32, 65536], tables too short for n, null tables
+    """Block sizes that are not a power of two in [16, 65536], tables too short for n, null tables
     and fp32 caches are turned away before any launch (no GPU needed: the checks come first)."""
     import ctypes
     from paper_2510_00636_amd.binding import EaPaged, make_params, EA_BF16, EA_F32
@@ -135,7 +135,7 @@ def test_paged_arguments_are_checked_on_the_host(lib):
         return lib.ea_score_paged(ctypes.byref(params), fake, fake, ctypes.byref(pg), n, fake, fake, fake, fake,
                                   ws_bytes, None)
     assert call(EaPaged(0x20000, 48, 100, 100)) == 2          # not a power of two
-    assert call(EaPaged(0x20000, 16, 1000, 1000)) == 2        # below a tile of 32 keys
+    assert call(EaPaged(0x20000, 8, 1000, 1000)) == 2         # below half a tile of 32 keys
     assert call(EaPaged(0x20000, 64, 10, 100)) == 1           # 10 blocks of 64 rows cannot hold 4096
     assert call(EaPaged(0, 64, 100, 100)) == 1                # no table
     assert call(EaPaged(0x20000, 64, 100, 0)) == 1            # empty pool

@@ -746,7 +746,9 @@ def _paged_setup(cfg, lay, bs, seed):
 
 
 @pytest.mark.parametrize("name,n,bs", [("c2mini", 3000, 32), ("c2mini", 2049, 256), ("c4mini", 1500, 64),
-                                      ("c5mini", 1100, 128), ("d64bf16", 700, 1024), ("c2mini", 17, 32)])
+                                      ("c5mini", 1100, 128), ("d64bf16", 700, 1024), ("c2mini", 17, 32),
+                                      ("c2mini", 3000, 16), ("c4mini", 1511, 16), ("d64bf16", 700, 16),
+                                      ("c5mini", 1097, 16), ("c2mini", 15, 16), ("c2mini", 48, 16)])
 def test_score_paged(name, n, bs):
     """ea_score over block pools behind a shuffled block table: same scores as the oracle gives for
     the logical rows (the rows of a sequence's last block beyond n, and the pool's spare blocks,
@@ -774,7 +776,8 @@ def test_score_paged(name, n, bs):
 
 
 @pytest.mark.parametrize("order_free", [0, 1])
-@pytest.mark.parametrize("name,n,bs", [("c2mini", 3000, 32), ("c4mini", 1500, 64), ("c5mini", 1100, 128)])
+@pytest.mark.parametrize("name,n,bs", [("c2mini", 3000, 32), ("c4mini", 1500, 64), ("c5mini", 1100, 128),
+                                      ("c2mini", 2990, 16), ("c4mini", 1500, 16)])
 def test_compress_layer_paged(name, n, bs, order_free):
     """The whole path over a paged cache: scores, kept set and the compacted logical rows equal
     what the oracle gives on the contiguous view; pool rows outside the kept prefix are untouched."""
