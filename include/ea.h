@@ -178,6 +178,17 @@ ea_status ea_select_adaptive(const ea_params* p, const float* scores, int64_t n,
                              int64_t floor, int32_t* idx, int32_t* lengths, void* ws, size_t ws_bytes,
                              void* stream);
 
+/* ea_compress_layer with the head-adaptive budget (the set-up of the paper's reported results,
+ * Sec. 2.2 "Head-Adaptive Compression" and Sec. 3.1): statistics -> scores -> ea_select_adaptive ->
+ * ragged in-place compaction, on `stream`, no host synchronisation.  idx_out [B, Hkv, n] and
+ * lengths_out [B, Hkv] (both required, DEVICE) are those of ea_select_adaptive; afterwards head
+ * (b, h) holds lengths_out[b, h] rows.  scores_out ([B, Hkv, n]) may be NULL. */
+ea_status ea_compress_layer_adaptive(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                                     const double* inv_freq, int64_t t_next, void* k, void* v, int64_t n,
+                                     int64_t n_cap, int64_t n_keep, int64_t floor, float* scores_out,
+                                     int32_t* idx_out, int32_t* lengths_out, void* ws, size_t ws_bytes,
+                                     void* stream);
+
 /* Listing 1's gather with a kept count per head, in place: row idx[b,h,j] of head (b,h) moves to
  * row j for j < lengths[b,h] (idx, lengths as written by ea_select_adaptive).  Rows from
  * lengths[b,h] on are left as they were. */

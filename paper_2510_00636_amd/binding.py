@@ -70,6 +70,9 @@ def load_library():
     lib.ea_compress_layer.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, VP, VP, VP, SZ, VP]
     lib.ea_select_adaptive.restype = ctypes.c_int
     lib.ea_select_adaptive.argtypes = [P, VP, I64, I64, I64, VP, VP, VP, SZ, VP]
+    lib.ea_compress_layer_adaptive.restype = ctypes.c_int
+    lib.ea_compress_layer_adaptive.argtypes = [P, VP, I64, I64, VP, I64, VP, VP, I64, I64, I64, I64, VP, VP, VP, VP,
+                                               SZ, VP]
     lib.ea_compact_ragged.restype = ctypes.c_int
     lib.ea_compact_ragged.argtypes = [P, VP, VP, I64, I64, VP, VP, VP, SZ, VP]
     lib.ea_score_baseline.restype = ctypes.c_int
@@ -213,6 +216,15 @@ def select_adaptive(p, scores, n, n_keep_, floor, idx, lengths, ws, stream=None)
     _check(load_library().ea_select_adaptive(ctypes.byref(p), _ptr(scores), int(n), int(n_keep_), int(floor),
                                              _ptr(idx), _ptr(lengths), _ptr(ws), _nbytes(ws),
                                              _stream(stream)), "ea_select_adaptive")
+
+
+def compress_layer_adaptive(p, q_win, window, q_pos0, inv_freq, t_next, k, v, n, n_cap, n_keep_, floor,
+                            scores_out, idx_out, lengths_out, ws, stream=None):
+    _check(load_library().ea_compress_layer_adaptive(ctypes.byref(p), _ptr(q_win), int(window), int(q_pos0),
+                                                     _ptr(inv_freq), int(t_next), _ptr(k), _ptr(v), int(n),
+                                                     int(n_cap), int(n_keep_), int(floor), _ptr(scores_out),
+                                                     _ptr(idx_out), _ptr(lengths_out), _ptr(ws), _nbytes(ws),
+                                                     _stream(stream)), "ea_compress_layer_adaptive")
 
 
 def compact_ragged(p, k, v, n, n_cap, idx, lengths, ws, stream=None):

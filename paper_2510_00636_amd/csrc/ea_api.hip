@@ -389,27 +389,17 @@ ea_status ea_compress_layer(const ea_params* p, const void* q_win, int64_t windo
                        scores_out, idx_out, ws, ws_bytes, stream, nullptr);
 }
 
-ea_status ea_select_adaptive(const ea_params* p, const float* scores, int64_t n, int64_t n_keep,
-                             int64_t floor, int32_t* idx, int32_t* lengths, void* ws, size_t ws_bytes,
-                             void* stream) {
-  Dims d;
-  ea_status s = check_params(p, &d);
-  if (s != EA_OK) return s;
-  if (n < 1 || n > kMaxN || n_keep < 0 || n_keep > n || floor < 0 || floor > n_keep) return EA_ERR_INVALID_ARG;
-  if (!aligned16(scores) || !aligned16(idx) || !lengths || ((uintptr_t)lengths & 3u)) return EA_ERR_INVALID_ARG;
-  if ((int64_t)d.Hkv * n > kMaxN) return EA_ERR_UNSUPPORTED;      // the pooled list of a layer
-  WsLayout L;
-  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
-  hipStream_t st = (hipStream_t)stream;
-  char* w = (char*)ws;
+// Pooled selection of ea_select_adaptive on the caller's stream.  `lifted`: a buffer of units * n
+// floats that is not `scores` (only used with a floor); `top`: units * floor ints of scratch.
+static ea_status run_select_adaptive(const Dims& d, const float* scores, int64_t n, int64_t n_keep, int64_t floor,
+                                     int32_t* idx, int32_t* lengths, float* lifted, int32_t* top, char* w,
+                                     const WsLayout& L, hipStream_t st) {
   uint32_t* hist = (uint32_t*)(w + L.hist);
   uint32_t* blk = (uint32_t*)(w + L.blk);
   int32_t* flat = (int32_t*)(w + L.idx);                // [B][Hkv * n_keep], ascending in [0, Hkv * n)
   const float* pooled = scores;
   if (floor > 0 && n_keep > 0) {
     // every head's own best `floor` pairs, then a copy of the scores with those lifted to +inf
-    int32_t* top = (int32_t*)(w + L.logits);            // [units][floor]
-    float* lifted = (float*)(w + L.scores);
     EA_TRY(launch_zero(hist, hist_words(d), st));
     EA_TRY(launch_select(d, scores, n, floor, top, hist, blk, false, st));
     EA_TRY(hipMemcpyAsync(lifted, scores, (size_t)d.units() * n * sizeof(float), hipMemcpyDeviceToDevice, st));
@@ -424,6 +414,61 @@ ea_status ea_select_adaptive(const ea_params* p, const float* scores, int64_t n,
     EA_TRY(launch_select(layer, pooled, (int64_t)d.Hkv * n, (int64_t)d.Hkv * n_keep, flat, hist, blk, false, st));
   }
   EA_TRY(launch_split_pooled(flat, d.B, d.Hkv, n, n_keep, idx, lengths, st));
+  return EA_OK;
+}
+
+ea_status ea_select_adaptive(const ea_params* p, const float* scores, int64_t n, int64_t n_keep,
+                             int64_t floor, int32_t* idx, int32_t* lengths, void* ws, size_t ws_bytes,
+                             void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (n < 1 || n > kMaxN || n_keep < 0 || n_keep > n || floor < 0 || floor > n_keep) return EA_ERR_INVALID_ARG;
+  if (!aligned16(scores) || !aligned16(idx) || !lengths || ((uintptr_t)lengths & 3u)) return EA_ERR_INVALID_ARG;
+  if ((int64_t)d.Hkv * n > kMaxN) return EA_ERR_UNSUPPORTED;      // the pooled list of a layer
+  WsLayout L;
+  if ((s = check_ws(d, n, 1, ws, ws_bytes, &L)) != EA_OK) return s;
+  char* w = (char*)ws;
+  return run_select_adaptive(d, scores, n, n_keep, floor, idx, lengths, (float*)(w + L.scores),
+                             (int32_t*)(w + L.logits), w, L, (hipStream_t)stream);
+}
+
+ea_status ea_compress_layer_adaptive(const ea_params* p, const void* q_win, int64_t window, int64_t q_pos0,
+                                     const double* inv_freq, int64_t t_next, void* k, void* v, int64_t n,
+                                     int64_t n_cap, int64_t n_keep, int64_t floor, float* scores_out,
+                                     int32_t* idx_out, int32_t* lengths_out, void* ws, size_t ws_bytes,
+                                     void* stream) {
+  Dims d;
+  ea_status s = check_params(p, &d);
+  if (s != EA_OK) return s;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || k == v || !inv_freq || ((uintptr_t)inv_freq & 7u))
+    return EA_ERR_INVALID_ARG;
+  if ((scores_out && !aligned16(scores_out)) || !aligned16(idx_out) || !lengths_out || ((uintptr_t)lengths_out & 3u))
+    return EA_ERR_INVALID_ARG;
+  if (window < 1 + d.ddof || q_pos0 < 0 || t_next < 0) return EA_ERR_INVALID_ARG;
+  if (window > kMaxWindow) return EA_ERR_UNSUPPORTED;
+  if (n < 1 || n > n_cap || n > kMaxN || n_keep < 0 || n_keep > n || floor < 0 || floor > n_keep)
+    return EA_ERR_INVALID_ARG;
+  if ((int64_t)d.Hkv * n > kMaxN) return EA_ERR_UNSUPPORTED;
+  if (partly_overlap(k, v, (size_t)d.units() * (size_t)n_cap * d.D * d.esize())) return EA_ERR_INVALID_ARG;
+  WsLayout L;
+  if ((s = check_ws(d, n, window, ws, ws_bytes, &L)) != EA_OK) return s;
+  hipStream_t st = (hipStream_t)stream;
+  char* w = (char*)ws;
+  float* mu = (float*)(w + L.mu);
+  float* sigma = (float*)(w + L.sigma);
+  float* scores = scores_out ? scores_out : (float*)(w + L.scores);
+  if ((s = run_stats(d, q_win, window, q_pos0, inv_freq, t_next, mu, sigma, w, L, st)) != EA_OK) return s;
+  if ((s = run_score(d, k, v, n, n_cap, mu, sigma, scores, nullptr, false, w, L, st)) != EA_OK) return s;
+  // after pass B the logit and value-norm scratch is free: the floor's lists and the lifted copy
+  // of the scores go there
+  if ((s = run_select_adaptive(d, scores, n, n_keep, floor, idx_out, lengths_out, (float*)(w + L.vnorm),
+                               (int32_t*)(w + L.logits), w, L, st)) != EA_OK)
+    return s;
+  uint32_t* flags = (uint32_t*)(w + L.flags);
+  uint32_t* status = (uint32_t*)(w + L.hist) + 2 * kSelBins + kStatusSlot;
+  EA_TRY(launch_zero(flags, flag_words(d, n), st));
+  EA_TRY(launch_compact(d, k, v, n, n_cap, idx_out, n, k, v, flags, status, st, lengths_out, n));
   return EA_OK;
 }
 

@@ -946,3 +946,52 @@ def test_compact_moves_fp8_rows():
         rperm = X.unordered_perm(keep, len(keep))
         assert np.array_equal(kd.cpu().numpy()[:, :, :len(keep)], k8[:, :, rperm])
         assert np.array_equal(vd.cpu().numpy()[:, :, :len(keep)], v8[:, :, rperm])
+
+
+# ------------------------------------------------------------------- fused pass with head-adaptive budgets
+@pytest.mark.parametrize("name,n,floor", [("c2mini", 3000, 0), ("c2mini", 3000, 200), ("c4mini", 1500, 64),
+                                          ("c5mini", 1100, 0), ("c1", 1024, 100)])
+def test_compress_layer_adaptive(name, n, floor):
+    """statistics -> scores -> pooled selection with a floor -> ragged compaction in one call: scores
+    against the oracle, lists and lengths bit-exact against the oracle's rule applied to the call's
+    own scores, bytes against the ragged gather."""
+    import torch
+    from oracle import ea_extensions as X
+    cfg, kw = MINI[name]
+    lay = make_layer(cfg, **dict(kw, n=n))
+    w = lay["window"]
+    n_keep = int(n * 0.4)
+    B, H = cfg.batch, cfg.n_kv_heads
+    p = P.params_for(cfg, epsilon=0.02)
+    ws = P.workspace(p, n, w)
+    kd, vd = P.to_dev(lay["k"]), P.to_dev(lay["v"])
+    sc = torch.empty(B, H, n, dtype=torch.float32, device="cuda")
+    idx = torch.full((B, H, n), -7, dtype=torch.int32, device="cuda")
+    lengths = torch.full((B, H), -1, dtype=torch.int32, device="cuda")
+    ea.compress_layer_adaptive(p, P.to_dev(lay["q_win"]), w, lay["q_pos0"], P.to_dev(lay["inv_freq"]), lay["t_next"],
+                               kd, vd, n, n, n_keep, floor, sc, idx, lengths, ws)
+    torch.cuda.synchronize()
+    assert ea.debug_status(p, n, w, ws) == 0
+    rmu, rsg = _oracle_stats(cfg, lay)
+    ref_sc = O.scores(widen(lay["k"]), widen(lay["v"]), rmu, rsg, 0.02)
+    gs = sc.cpu().numpy()
+    P.check_scores(gs, ref_sc, TOL[cfg.dtype])
+    rl, rk = X.select_adaptive(gs.astype(np.float64), n_keep, floor)
+    gl, gi = lengths.cpu().numpy(), idx.cpu().numpy()
+    assert np.array_equal(gl, rl) and gl.sum(axis=1).tolist() == [H * n_keep] * B
+    ko, vo = P.to_host(kd), P.to_host(vd)
+    ref = X.compact_ragged(lay["k"], lay["v"], rk)
+    for b in range(B):
+        for h in range(H):
+            m = gl[b, h]
+            assert m >= floor
+            assert np.array_equal(gi[b, h, :m], rk[b][h]), (b, h)
+            assert np.array_equal(ko[b, h, :m], ref[b][h][0]) and np.array_equal(vo[b, h, :m], ref[b][h][1])
+            assert np.array_equal(ko[b, h, m:], lay["k"][b, h, m:])
+    # the same call without the optional scores gives the same cache
+    kd2, vd2 = P.to_dev(lay["k"]), P.to_dev(lay["v"])
+    idx2, len2 = torch.empty_like(idx), torch.empty_like(lengths)
+    ea.compress_layer_adaptive(p, P.to_dev(lay["q_win"]), w, lay["q_pos0"], P.to_dev(lay["inv_freq"]), lay["t_next"],
+                               kd2, vd2, n, n, n_keep, floor, None, idx2, len2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(len2, lengths) and torch.equal(kd2, kd) and torch.equal(vd2, vd)
