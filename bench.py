@@ -64,6 +64,9 @@ def parse():
     ap.add_argument("--paged", type=int, default=0, metavar="BLOCK",
                     help="prefill shapes: keep the cache in block pools of BLOCK rows behind a shuffled block "
                          "table and time ea_compress_layer_paged (0 = contiguous tensors)")
+    ap.add_argument("--adaptive", type=float, default=-1.0, metavar="FLOOR",
+                    help="prefill shapes: time ea_compress_layer_adaptive (one budget per layer shared by its KV "
+                         "heads); FLOOR in [0, 1] = the share of n_keep every head keeps whatever its scores")
     ap.add_argument("--fp8", action="store_true",
                     help="prefill shapes: store K and V as e4m3 bytes with per-head scales and time "
                          "ea_compress_layer_fp8 (half the bytes per pair)")
@@ -252,6 +255,18 @@ def run_prefill(a, torch, ea, cfg):
                                   scales[0][l:l + LB], scales[1][l:l + LB], n, n, n_keep, 0, None, None, None,
                                   wss[i % ns], stream=streams[i % ns])
 
+    adapt = None
+    if a.adaptive >= 0:
+        floor = int(a.adaptive * n_keep)
+        adapt = [(torch.empty(B * LB, Hkv, n, dtype=torch.int32, device=dev),
+                  torch.empty(B * LB, Hkv, dtype=torch.int32, device=dev)) for _ in range(ns)]
+
+        def step_adaptive():
+            for i, l in enumerate(range(0, L, LB)):
+                ea.compress_layer_adaptive(p, q[l:l + LB], w, q_pos0, inv, t_next, k[l:l + LB], v[l:l + LB], n, n,
+                                           n_keep, floor, None, adapt[i % ns][0], adapt[i % ns][1], wss[i % ns],
+                                           stream=streams[i % ns])
+
     def step_paged():
         for i, l in enumerate(range(0, L, LB)):
             ea.compress_layer_paged(p, q[l:l + LB], w, q_pos0, inv, t_next, k, v, pg_of(l, LB), n, n_keep, 0, None,
@@ -262,6 +277,8 @@ def run_prefill(a, torch, ea, cfg):
             return step_paged()
         if a.fp8:
             return step_fp8()
+        if adapt is not None:
+            return step_adaptive()
         # call i runs on stream i % ns with that stream's workspace; the caller synchronises the
         # device before and after a step
         for i, l in enumerate(range(0, L, LB)):
@@ -292,7 +309,7 @@ def run_prefill(a, torch, ea, cfg):
     frac = lambda ms: pairs * bytes_per_pair / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
     layer_by_layer = None
-    if a.paged or a.fp8:
+    if a.paged or a.fp8 or adapt is not None:
         out = {"metric": "KV pairs scored+compacted/sec", "value": round(pairs / (ms_per_step * 1e-3) / 1e9, 4),
                "unit": "G pairs/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
                "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -300,6 +317,11 @@ def run_prefill(a, torch, ea, cfg):
                "config": {"workload": ("%s, paged: %d layers x %d KV heads x %d tokens x d%d in pools of %d-row blocks "
                                        "behind a shuffled block table, ratio %.2f, %d layer(s) per call, %d streams" %
                                        (cfg.name, L, Hkv * B, n, d, a.paged, a.ratio, LB, ns)) if a.paged else
+                                      ("%s, head-adaptive budgets (ea_compress_layer_adaptive, floor %d of %d per head): "
+                                       "%d layers x %d KV heads x %d tokens x d%d, ratio %.2f, %d layer(s) per call, %d "
+                                       "streams; lengths of the last call %s" %
+                                       (cfg.name, int(a.adaptive * n_keep), n_keep, L, Hkv * B, n, d, a.ratio, LB, ns,
+                                        adapt[(L // LB - 1) % ns][1][0].tolist())) if adapt is not None else
                                       ("%s, K and V stored as e4m3 bytes with per-head scales: %d layers x %d KV heads x "
                                        "%d tokens x d%d, ratio %.2f, %d layer(s) per call, %d streams" %
                                        (cfg.name, L, Hkv * B, n, d, a.ratio, LB, ns)),
