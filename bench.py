@@ -26,6 +26,10 @@ instrumented steps, `hbm_copy_ceiling_GBs` (a plain 2 GiB device copy on this bo
 
     python bench.py [--steps K] [--warmup W] [--workload c3|c2|c4|c5] [--ratio R] [--layers L]
                     [--streams S] [--layer-batch LB] [--ordered] [--graph] [--skip-layer-by-layer]
+                    [--paged BLOCK | --fp8 | --adaptive FLOOR | --scorer knorm|streaming|keydiff | --literal]
+The last line's options time variants of the pass (paged or 8-bit caches, head-adaptive budgets, a
+comparison scorer in front of the same select + compact, Eq. 5 / Eq. 9 as printed from hidden states,
+W_Q and W_o); their JSON line names the variant in config.workload.
 """
 import argparse
 import hashlib
@@ -67,6 +71,13 @@ def parse():
     ap.add_argument("--adaptive", type=float, default=-1.0, metavar="FLOOR",
                     help="prefill shapes: time ea_compress_layer_adaptive (one budget per layer shared by its KV "
                          "heads); FLOOR in [0, 1] = the share of n_keep every head keeps whatever its scores")
+    ap.add_argument("--scorer", default="", choices=["", "knorm", "streaming", "keydiff"],
+                    help="the pass with one of the comparison scorers in front of the same select + compact "
+                         "(ea_score_baseline, ea_select, ea_compact per call)")
+    ap.add_argument("--literal", action="store_true",
+                    help="the pass as Eq. 5 and Eq. 9 are printed: statistics from a hidden-state buffer and W_Q, "
+                         "scores weighted by ||W_o v|| (one layer per call: every layer has weights of its own)")
+    ap.add_argument("--d-model", type=int, default=4096, help="--literal: width of the hidden states")
     ap.add_argument("--fp8", action="store_true",
                     help="prefill shapes: store K and V as e4m3 bytes with per-head scales and time "
                          "ea_compress_layer_fp8 (half the bytes per pair)")
@@ -190,7 +201,7 @@ def run_prefill(a, torch, ea, cfg):
     L = a.layers or cfg.layers
     B, Hq, Hkv, d, n, w = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n, cfg.window
     n_keep = ea.n_keep(n, a.ratio)
-    LB = max(1, a.layer_batch or 4)
+    LB = 1 if a.literal else max(1, a.layer_batch or 4)
     while L % LB:
         LB -= 1
     mk = lambda lb: ea.make_params(B * lb, Hq, Hkv, d, ea.EA_BF16, horizon_T=cfg.horizon_T, epsilon=a.epsilon)
@@ -267,6 +278,44 @@ def run_prefill(a, torch, ea, cfg):
                                            n_keep, floor, None, adapt[i % ns][0], adapt[i % ns][1], wss[i % ns],
                                            stream=streams[i % ns])
 
+    alt = None
+    if a.scorer or a.literal:
+        sc_b = [torch.empty(B * LB, Hkv, n, dtype=torch.float32, device=dev) for _ in range(ns)]
+        ix_b = [torch.empty(B * LB, Hkv, n_keep, dtype=torch.int32, device=dev) for _ in range(ns)]
+    if a.scorer:
+        kind = {"knorm": ea.SCORER_KNORM, "streaming": ea.SCORER_STREAMING, "keydiff": ea.SCORER_KEYDIFF}[a.scorer]
+
+        def alt():
+            for i, l in enumerate(range(0, L, LB)):
+                j, st = i % ns, streams[i % ns]
+                ea.score_baseline(p, kind, k[l:l + LB], n, n, 4, sc_b[j], wss[j], stream=st)
+                ea.select(p, sc_b[j], n, n_keep, ix_b[j], wss[j], stream=st)
+                ea.compact(p, k[l:l + LB], v[l:l + LB], n, n, ix_b[j], n_keep, k[l:l + LB], v[l:l + LB], wss[j],
+                           stream=st)
+    if a.literal:
+        dm = a.d_model
+        gen = torch.Generator(device=dev).manual_seed(11)
+        rnd = lambda *sh: torch.randn(*sh, device=dev, generator=gen)
+        hidden = (rnd(L, B, w, dm) * 1.5 + rnd(L, 1, 1, dm)).to(torch.bfloat16)
+        w_q = (rnd(L, Hq, d, dm) / dm ** 0.5).to(torch.bfloat16)
+        w_o = (rnd(L, Hq, dm, d) / d ** 0.5).to(torch.bfloat16)
+        # W_o^T W_o is a constant of the model: taken once per layer, outside the timed region
+        gram = torch.empty(L, Hq, d, d, dtype=torch.float32, device=dev)
+        for l in range(L):
+            ea.wo_gram(p, w_o[l], dm, gram[l])
+        mu_b = [torch.empty(B, Hq, d, dtype=torch.float32, device=dev) for _ in range(ns)]
+        sg_b = [torch.empty(B, Hq, d, d, dtype=torch.float32, device=dev) for _ in range(ns)]
+        wn_b = [torch.empty(B, Hq, n, dtype=torch.float32, device=dev) for _ in range(ns)]
+
+        def alt():
+            for l in range(L):
+                j, st = l % ns, streams[l % ns]
+                ea.query_stats_hidden(p, hidden[l], w_q[l], dm, w, inv, t_next, mu_b[j], sg_b[j], wss[j], stream=st)
+                ea.value_norms_wo(p, v[l], n, n, gram[l], wn_b[j], wss[j], stream=st)
+                ea.score_wo(p, k[l], v[l], n, n, mu_b[j], sg_b[j], wn_b[j], sc_b[j], wss[j], stream=st)
+                ea.select(p, sc_b[j], n, n_keep, ix_b[j], wss[j], stream=st)
+                ea.compact(p, k[l], v[l], n, n, ix_b[j], n_keep, k[l], v[l], wss[j], stream=st)
+
     def step_paged():
         for i, l in enumerate(range(0, L, LB)):
             ea.compress_layer_paged(p, q[l:l + LB], w, q_pos0, inv, t_next, k, v, pg_of(l, LB), n, n_keep, 0, None,
@@ -279,6 +328,8 @@ def run_prefill(a, torch, ea, cfg):
             return step_fp8()
         if adapt is not None:
             return step_adaptive()
+        if alt is not None:
+            return alt()
         # call i runs on stream i % ns with that stream's workspace; the caller synchronises the
         # device before and after a step
         for i, l in enumerate(range(0, L, LB)):
@@ -309,6 +360,22 @@ def run_prefill(a, torch, ea, cfg):
     frac = lambda ms: pairs * bytes_per_pair / (ms * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
     layer_by_layer = None
+    if alt is not None:
+        if a.scorer:
+            bpp = 2 * d * 2 * ((0 if a.scorer == "streaming" else 0.5) + 2 * f)   # K read once (not at all by position)
+            what = ("%s scores (ea_score_baseline) + ea_select + ea_compact" % a.scorer)
+        else:
+            bpp = 2 * d * 2 * (1.5 + 2 * f)                                      # V is read twice: ||W_o v||, then pass A
+            what = ("Eq. 5 from hidden states [%d, %d] and W_Q, Eq. 9 with ||W_o v|| (ea_query_stats_hidden, "
+                    "ea_value_norms_wo, ea_score_wo, ea_select, ea_compact)" % (w, a.d_model))
+        return {"metric": "KV pairs scored+compacted/sec", "value": round(pairs / (ms_per_step * 1e-3) / 1e9, 4),
+                "unit": "G pairs/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+                "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                "dtype": "bf16", "data": "synthetic",
+                "config": {"workload": "%s, %s: %d layers x %d KV heads x %d tokens x d%d, ratio %.2f, %d layer(s) per "
+                                       "call, %d streams" % (cfg.name, what, L, Hkv * B, n, d, a.ratio, LB, ns),
+                           "pairs_per_step": pairs, "bytes_per_pair": bpp},
+                "path_hbm_frac": round(pairs * bpp / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4)}
     if a.paged or a.fp8 or adapt is not None:
         out = {"metric": "KV pairs scored+compacted/sec", "value": round(pairs / (ms_per_step * 1e-3) / 1e9, 4),
                "unit": "G pairs/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,

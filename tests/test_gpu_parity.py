@@ -666,7 +666,9 @@ def test_select_adaptive_and_ragged_compaction(n, n_keep, floor):
 
 
 # ------------------------------------------------------------------- hidden-state front end (Eq. 5 as printed)
-@pytest.mark.parametrize("dt,d,w,dm", [("bf16", 128, 128, 512), ("f32", 64, 40, 200), ("bf16", 256, 70, 96)])
+@pytest.mark.parametrize("dt,d,w,dm", [("bf16", 128, 128, 512), ("f32", 64, 40, 200), ("bf16", 256, 70, 96),
+                                      ("bf16", 128, 300, 4096), ("bf16", 64, 33, 72), ("bf16", 128, 50, 130),
+                                      ("bf16", 128, 2, 64)])
 def test_query_stats_from_hidden_states(dt, d, w, dm):
     """mu, Sigma from a hidden-state buffer and W_Q against the oracle's literal Eq. 5 (mean and
     covariance of the hidden states, then W_Q, then R-bar)."""
