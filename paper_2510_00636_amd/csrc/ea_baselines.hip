@@ -58,6 +58,7 @@ __device__ __forceinline__ float row_sum16(float x) {
 }
 
 constexpr int kBaseRowsPerWg = 128;     // 16 rows at a time, 8 rounds
+constexpr int kKeydiffRowsPerWg = 1024; // KeyDiff's second pass: the anchor is rebuilt once per workgroup
 
 template <int D, bool BF16>
 __global__ __launch_bounds__(256) void k_knorm(const void* __restrict__ k, long long n, long long n_cap,
@@ -98,13 +99,21 @@ __global__ __launch_bounds__(256) void k_keydiff_partial(const void* __restrict_
   float acc[RP::NP * RP::W];
 #pragma unroll
   for (int i = 0; i < RP::NP * RP::W; ++i) acc[i] = 0.f;
-  for (long long row = r0 + rw; row < r1; row += 16) {
-    RP p;
-    p.load(base, row, l);
-    const float ss = row_sum16(p.sumsq());
-    const float inv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+  // eight rows per lane group in flight; they are added in the order a one-row loop would take them
+  constexpr int U = 8;
+  for (long long row = r0 + rw; row < r1; row += 16 * U) {
+    RP p[U];
 #pragma unroll
-    for (int i = 0; i < RP::NP * RP::W; ++i) acc[i] = fmaf(p.x[i], inv, acc[i]);
+    for (int u = 0; u < U; ++u) p[u].load(base, min(row + 16 * u, n - 1), l);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (row + 16 * u < r1) {
+        const float ss = row_sum16(p[u].sumsq());
+        const float inv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+#pragma unroll
+        for (int i = 0; i < RP::NP * RP::W; ++i) acc[i] = fmaf(p[u].x[i], inv, acc[i]);
+      }
+    }
   }
 #pragma unroll
   for (int j = 0; j < RP::NP; ++j)
@@ -133,7 +142,7 @@ __global__ __launch_bounds__(256) void k_keydiff_score(const void* __restrict__ 
   __shared__ float s_inv;
   const int tid = threadIdx.x, l = tid & 15, rw = tid >> 4;
   const int unit = blockIdx.x % units;
-  const long long r0 = (long long)(blockIdx.x / units) * kBaseRowsPerWg;
+  const long long r0 = (long long)(blockIdx.x / units) * kKeydiffRowsPerWg;
   for (int c = tid; c < D; c += 256) {
     float s = 0.f;
     for (int q = 0; q < nchunk; ++q) s += partial[((size_t)unit * nchunk + q) * D + c];
@@ -149,23 +158,36 @@ __global__ __launch_bounds__(256) void k_keydiff_score(const void* __restrict__ 
   __syncthreads();
   const float inv_a = s_inv;
   const char* base = (const char*)k + (size_t)unit * n_cap * D * (BF16 ? 2 : 4);
+  // the lane's channels of the anchor, once
+  float an[RP::NP * RP::W];
 #pragma unroll
-  for (int it = 0; it < kBaseRowsPerWg / 16; ++it) {
-    const long long row = r0 + it * 16 + rw;
-    RP p;
-    p.load(base, min(row, n - 1), l);
+  for (int j = 0; j < RP::NP; ++j)
+#pragma unroll
+    for (int e = 0; e < RP::W; ++e) {
+      const int c = RP::W * l + 16 * RP::W * j + e;
+      an[RP::W * j + e] = c < D ? s_a[c] : 0.f;
+    }
+  for (int it0 = 0; it0 < kKeydiffRowsPerWg / 16 && r0 + it0 * 16 < n; it0 += 8) {
+  RP pp[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) pp[u].load(base, min(r0 + (it0 + u) * 16 + rw, n - 1), l);
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const long long row = r0 + (it0 + u) * 16 + rw;
+    const RP& p = pp[u];
     float dot = 0.f;
 #pragma unroll
     for (int j = 0; j < RP::NP; ++j)
 #pragma unroll
       for (int e = 0; e < RP::W; ++e) {
         const int c = RP::W * l + 16 * RP::W * j + e;
-        if (c < D) dot = fmaf(p.x[RP::W * j + e], s_a[c], dot);
+        if (c < D) dot = fmaf(p.x[RP::W * j + e], an[RP::W * j + e], dot);
       }
     const float ss = row_sum16(p.sumsq());
     dot = row_sum16(dot);
     const float cosv = ss > 0.f ? dot * inv_a / sqrtf(ss) : 0.f;
     if (l == 0 && row < n) scores[(size_t)unit * n + row] = 1.0f - cosv;
+  }
   }
 }
 
@@ -181,7 +203,8 @@ static hipError_t launch_baseline_t(const Dims& d, int kind, const void* k, int6
     const int rows = (int)((n + nchunk - 1) / nchunk);
     nchunk = (int)((n + rows - 1) / rows);
     k_keydiff_partial<D, BF16><<<nchunk * d.units(), 256, 0, st>>>(k, n, n_cap, d.units(), rows, scratch);
-    k_keydiff_score<D, BF16><<<nblk * d.units(), 256, 0, st>>>(k, n, n_cap, d.units(), nchunk, scratch, scores);
+    const unsigned nblk2 = (unsigned)((n + kKeydiffRowsPerWg - 1) / kKeydiffRowsPerWg);
+    k_keydiff_score<D, BF16><<<nblk2 * d.units(), 256, 0, st>>>(k, n, n_cap, d.units(), nchunk, scratch, scores);
   }
   return hipGetLastError();
 }
