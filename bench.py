@@ -365,7 +365,7 @@ def run_prefill(a, torch, ea, cfg):
             bpp = 2 * d * 2 * ((0 if a.scorer == "streaming" else 0.5) + 2 * f)   # K read once (not at all by position)
             what = ("%s scores (ea_score_baseline) + ea_select + ea_compact" % a.scorer)
         else:
-            bpp = 2 * d * 2 * (1.5 + 2 * f)                                      # V is read twice: ||W_o v||, then pass A
+            bpp = 2 * d * 2 * (1 + 2 * f)        # V once for ||W_o v||, K once for the logits, kept rows read + written
             what = ("Eq. 5 from hidden states [%d, %d] and W_Q, Eq. 9 with ||W_o v|| (ea_query_stats_hidden, "
                     "ea_value_norms_wo, ea_score_wo, ea_select, ea_compact)" % (w, a.d_model))
         return {"metric": "KV pairs scored+compacted/sec", "value": round(pairs / (ms_per_step * 1e-3) / 1e9, 4),

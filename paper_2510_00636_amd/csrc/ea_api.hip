@@ -72,7 +72,7 @@ static ea_status run_score(const Dims& d, const void* k, const void* v, int64_t 
     if (ev) EA_TRY(hipEventRecord(ev[0], st));
     EA_TRY(launch_score_mfma(d, sp, k, v, n, n_cap, frags, post, (float*)(ws + L.logits), vnorm,
                              (float2*)(ws + L.part), hist + 2 * kSelBins + kTicketSlot, 3 * kSelBins,
-                             st, pm, kscale, vscale));
+                             st, pm, kscale, vscale, wnorm != nullptr || wnorm_out != nullptr));
     if (ev) EA_TRY(hipEventRecord(ev[1], st));
     if (wnorm_out) return launch_wnorm(ws + L.logits, 0, (size_t)d.qheads() * n, d.D, wnorm_out, st) == hipSuccess
                               ? EA_OK : EA_ERR_DEVICE;

@@ -29,7 +29,8 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
                              float* logits, float* vnorm, float2* part, uint32_t* tickets,
                              int ticket_stride, hipStream_t st, const PageMap* pm = nullptr,
-                             const float* kscale = nullptr, const float* vscale = nullptr);
+                             const float* kscale = nullptr, const float* vscale = nullptr, bool skip_v = false);
+// skip_v: V is neither read nor turned into norms (the caller weighs the pairs with norms of its own)
 // kscale, vscale [units] (nullable): per-head scales of caches stored as e4m3 bytes (d.kv_fp8)
 hipError_t launch_score_f32(const Dims& d, const void* k, const void* v, int64_t n, int64_t n_cap,
                             const float* mu, const float* sigma, double* logits, float* vnorm,

@@ -15,8 +15,9 @@ hipError_t launch_score_mfma(const Dims& d, const ScorePlan& sp, const void* k, 
                              int64_t n, int64_t n_cap, const uint4* frags, const float* post,
                              float* logits, float* vnorm, float2* part, uint32_t* tickets,
                              int ticket_stride, hipStream_t st, const PageMap* pm, const float* kscale,
-                             const float* vscale) {
+                             const float* vscale, bool skip_v) {
   ScoreArgs a;
+  a.skip_v = skip_v ? 1 : 0;
   a.pm = pm ? *pm : PageMap{nullptr, 0, 0, 1, 0};
   a.kscale = kscale;
   a.vscale = vscale;

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256, 2) void k_score_hw(ScoreArgs a) {
   const int t2 = bid / a.units;
   const int chunk = t2 % a.nchunk, pass = t2 / a.nchunk;
   const int g0 = pass * GH;
-  const bool do_v = pass == 0;
+  const bool do_v = pass == 0 && !a.skip_v;
   const int tpt = a.tpt, tsh = tpt == 4 ? 2 : 0;
   const int ntiles = (int)((a.n + 31) / 32);
   const int nblocks = (ntiles + tpt - 1) >> tsh;

@@ -39,6 +39,7 @@ struct ScoreArgs {
   PageMap pm;             // pm.table != nullptr: k and v are block pools (CLAMP instances only)
   const float* kscale;    // FP8 instances: real key = kscale[unit] * stored value (nullptr: 1)
   const float* vscale;    // likewise for the values
+  int skip_v;             // 1: the caller has its own per-pair weights; V is not read, vnorm not written
 };
 
 __device__ __forceinline__ half8 bf16x8_to_half8(u32x4 r) {
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(NW * 64) void k_score_mfma(ScoreArgs a) {
   const int t2 = bid / a.units;
   const int chunk = t2 % a.nchunk, pass = t2 / a.nchunk;
   const int g0 = pass * GH;
-  const bool do_v = pass == 0;
+  const bool do_v = pass == 0 && !a.skip_v;
 
   // Prologue order: tile tickets, then the loads of this (unit, pass)'s fragments, then the
   // first tile's K and V loads (they need the first ticket, which has had the fragment loads'
