@@ -418,12 +418,14 @@ hipError_t launch_mark_inf(float* scores, const int32_t* idx, int units, int64_t
   return hipGetLastError();
 }
 
-// One workgroup per (sequence, head): the head's stretch of the pooled ascending list is found by
-// two binary searches, then copied with the head's offset taken off.
+// kSplitChunks workgroups per (sequence, head): the head's stretch of the pooled ascending list is
+// found by two binary searches (every workgroup repeats them: forty loads), then copied with the
+// head's offset taken off, each workgroup one slice of it.
+constexpr int kSplitChunks = 32;
 __global__ __launch_bounds__(256) void k_split_pooled(const int32_t* __restrict__ flat, int H, long long n,
                                                       long long n_keep, int32_t* __restrict__ idx,
                                                       int32_t* __restrict__ lengths) {
-  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  const int b = blockIdx.x / H, h = blockIdx.x % H, chunk = blockIdx.y;
   const long long total = (long long)H * n_keep;
   const int32_t* f = flat + (size_t)b * total;
   auto lower = [&](long long key) {
@@ -435,14 +437,16 @@ __global__ __launch_bounds__(256) void k_split_pooled(const int32_t* __restrict_
     return lo;
   };
   const long long lo = lower((long long)h * n), hi = lower((long long)(h + 1) * n);
-  if (threadIdx.x == 0) lengths[blockIdx.x] = (int32_t)(hi - lo);
+  if (threadIdx.x == 0 && chunk == 0) lengths[blockIdx.x] = (int32_t)(hi - lo);
   int32_t* out = idx + (size_t)blockIdx.x * n;
-  for (long long j = lo + threadIdx.x; j < hi; j += 256) out[j - lo] = f[j] - (int32_t)(h * n);
+  const long long per = (hi - lo + kSplitChunks - 1) / kSplitChunks;
+  const long long j0 = lo + chunk * per, j1 = min(hi, j0 + per);
+  for (long long j = j0 + threadIdx.x; j < j1; j += 256) out[j - lo] = f[j] - (int32_t)(h * n);
 }
 
 hipError_t launch_split_pooled(const int32_t* flat, int B, int H, int64_t n, int64_t n_keep, int32_t* idx,
                                int32_t* lengths, hipStream_t st) {
-  k_split_pooled<<<B * H, 256, 0, st>>>(flat, H, n, n_keep, idx, lengths);
+  k_split_pooled<<<dim3(B * H, kSplitChunks), 256, 0, st>>>(flat, H, n, n_keep, idx, lengths);
   return hipGetLastError();
 }
 
