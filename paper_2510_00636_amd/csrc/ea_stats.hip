@@ -63,10 +63,10 @@ __global__ void k_rope_table(const double* __restrict__ inv_freq, long long q_po
 // The fp32 matrix-core work is what bounds the kernel for long windows (64 cycles per pair of
 // samples and tile): the triangle and the even deal over workgroups are what keep it short.
 constexpr int kStatsWC = 64;    // samples per LDS chunk
-template <int D> struct StatsTiling {
+template <int D, int PARTS_ = 0> struct StatsTiling {
   static constexpr int NCT = D / 32;                       // 32-column tiles across Sigma
   static constexpr int NT = NCT * (NCT + 1) / 2;           // tiles on and above the diagonal
-  static constexpr int PARTS = D <= 64 ? 1 : (D <= 128 ? 2 : 4);
+  static constexpr int PARTS = PARTS_ > 0 ? PARTS_ : D <= 64 ? 1 : (D <= 128 ? 2 : 4);
   static constexpr int TP = (NT + PARTS - 1) / PARTS;      // tiles per workgroup
   // A workgroup's first 4 WHOLE tiles go one (or WHOLE) to each wavefront; the SHARED tiles left
   // over are each split four ways by samples and the four partial tiles added at the end, so
@@ -370,8 +370,8 @@ typedef _Float16 stats_half2 __attribute__((ext_vector_type(2)));
 // chunk's queries and table rows in flight during the matrix-core loop)
 constexpr int stats_split_chunk(int D) { return D >= 256 ? 32 : 64; }
 
-template <int D, int LAYOUT>
-__global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats_split(const void* __restrict__ q_win, int w,
+template <int D, int LAYOUT, int PARTS = 0>
+__global__ __launch_bounds__(256, (D <= 128 && !(D == 128 && PARTS == 1) ? 3 : 2)) void k_stats_split(const void* __restrict__ q_win, int w,
                                                                          int ddof,
                                                                          const float2* __restrict__ tab,
                                                                          float* __restrict__ mu,
@@ -390,7 +390,7 @@ __global__ __launch_bounds__(256, (D <= 128 ? 3 : 2)) void k_stats_split(const v
   constexpr int BW = G8 >= 16 ? 1 : 16 / G8;          // blocks one wave-wide staging write spans
   auto swz_of_group = [](int gg) { return ITEMS >= 2 ? ((gg >> 1) * BW) % NB : 0; };
   auto group_of_channel = [](int c) { return LAYOUT ? c / 16 : (c % HALF) / 8; };
-  typedef StatsTiling<D> TL;
+  typedef StatsTiling<D, PARTS> TL;
   constexpr int NCT = TL::NCT, TPW = TL::SLOTS;
   static_assert(ITEMS >= 1 && 256 % G8 == 0, "one channel group per thread");
   static_assert(TL::SHARED * 4 * 16 * 64 * 4 <= 2 * D * P * 2, "partial tiles fit in the planes");
@@ -808,17 +808,29 @@ static hipError_t launch_stats_one(const Dims& d, const void* q_win, int w, cons
   return hipGetLastError();
 }
 
-template <int D, int LAYOUT>
-static hipError_t launch_stats_split_one(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
-                                         float* sigma, hipStream_t st) {
-  auto kern = k_stats_split<D, LAYOUT>;
+template <int D, int LAYOUT, int PARTS>
+static hipError_t launch_stats_split_parts(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
+                                           float* sigma, hipStream_t st) {
+  auto kern = k_stats_split<D, LAYOUT, PARTS>;
   const size_t lds = (size_t)2 * D * (stats_split_chunk(D) + 8) * sizeof(_Float16) + (size_t)(6 * D + 4) * sizeof(float);
   static LdsOptIn opt;
   hipError_t e = opt.ensure(reinterpret_cast<const void*>(kern), lds);
   if (e != hipSuccess) return e;
-  dim3 grid(d.qheads(), StatsTiling<D>::PARTS);
+  dim3 grid(d.qheads(), StatsTiling<D, PARTS>::PARTS);
   kern<<<grid, 256, lds, st>>>(q_win, w, d.ddof, tab, mu, sigma);
   return hipGetLastError();
+}
+// Every workgroup of a head stages all of the head's samples, so a head split over two workgroups
+// pays the staging twice: with enough heads to fill the chip (the decode-time shape: 960 per call)
+// one workgroup takes all ten tiles of a d = 128 head.
+constexpr int kStatsWholeHeadMin = 384;
+template <int D, int LAYOUT>
+static hipError_t launch_stats_split_one(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,
+                                         float* sigma, hipStream_t st) {
+  if constexpr (D == 128) {
+    if (d.qheads() >= kStatsWholeHeadMin) return launch_stats_split_parts<D, LAYOUT, 1>(d, q_win, w, tab, mu, sigma, st);
+  }
+  return launch_stats_split_parts<D, LAYOUT, 0>(d, q_win, w, tab, mu, sigma, st);
 }
 template <int D>
 static hipError_t launch_stats_split(const Dims& d, const void* q_win, int w, const float2* tab, float* mu,

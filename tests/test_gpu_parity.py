@@ -52,6 +52,18 @@ def test_query_stats_window_sizes(w, dt):
         P.check_stats(mu, sg, rmu, rsg)
 
 
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("w", [40, 130])
+def test_query_stats_many_heads(w, layout):
+    """With several hundred query heads per call one workgroup takes a whole d = 128 head (all ten
+    covariance tiles) instead of half of it: the decode-time shape, 40 query heads x many layers."""
+    cfg = CONFIGS["c2"].with_(head_dim=128, n_q_heads=40, n_kv_heads=8, batch=10)
+    lay = make_layer(cfg, n=w + 9, window=w, interleaved=bool(layout))
+    mu, sg = P.run_query_stats(cfg, lay, rope_layout=layout)
+    rmu, rsg = _oracle_stats(cfg, lay, **({"layout": O.INTERLEAVED} if layout else {}))
+    P.check_stats(mu, sg, rmu, rsg)
+
+
 @pytest.mark.parametrize("variant", ["interleaved", "ddof1", "pre_rope", "T1", "w1"])
 def test_query_stats_variants(variant):
     cfg = CONFIGS["c2"].with_(n_q_heads=4, n_kv_heads=2)
