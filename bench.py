@@ -97,10 +97,14 @@ def traffic_from_profile(name, layers_per_launch):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of this
     workload, or None: also None when the summary was taken for other kernel sources than the ones
     in the tree now (it names their hash), so a stale figure is never printed."""
-    path = os.path.join(ROOT, "profiles", "score_pass_a_%s_pmc.txt" % name)
-    try:
-        text = open(path).read()
-    except OSError:
+    text = None
+    for fn in ("score_pass_a_%s_pmc.txt", "score_pass_a_%s_kernel_stats_pmc.txt"):
+        try:
+            text = open(os.path.join(ROOT, "profiles", fn % name)).read()
+            break
+        except OSError:
+            pass
+    if text is None:
         return None
     if "kernel_source_sha256_16: %s" % kernel_source_hash() not in text:
         return None
