@@ -14,6 +14,9 @@ constexpr int kSelBins = 2048;        // radix-select digit width: 11 + 11 + 10 
 constexpr int kSelBlock = 4096;       // scores per workgroup in the select passes
 constexpr int kLseBlock = 2048;       // keys per softmax partial when the partials are taken from the stored logits
 constexpr int kCompactRows = 96;     // destination rows per workgroup chunk in ea_compact (not a power of two on purpose)
+// rows of 128 bytes (8-bit caches at d = 128, 16-bit at d = 64) come twice as many to a chunk: the
+// same 24 KiB per workgroup for its ticket, its flags and its index loads
+constexpr int compact_rows(int row_bytes) { return row_bytes <= 128 ? 2 * kCompactRows : kCompactRows; }
 
 struct Dims {
   int B, Hq, Hkv, G, D, half;

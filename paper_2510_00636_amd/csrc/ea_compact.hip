@@ -71,7 +71,9 @@ __device__ int first_true(int c, int lane, Pred pred) {
 template <int RB, bool PAGED>
 __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   constexpr int CPR = RB / 16;                 // 16-byte pieces per row
-  constexpr int NLD = kCompactRows * CPR / 256;
+  constexpr int ROWS = compact_rows(RB);       // destination rows per chunk
+  constexpr int NLD = ROWS * CPR / 256;
+  constexpr int NCHK = (ROWS + 63) / 64;
   __shared__ int s_c, s_lo, s_hi, s_ident, s_abort;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   const int c = s_c;
   const int unit = tu >> 1, tensor = tu & 1;
   const int n_keep = a.lengths ? a.lengths[unit] : a.n_keep;
-  const int j0 = c * kCompactRows, j1 = min(j0 + kCompactRows, n_keep);
+  const int j0 = c * ROWS, j1 = min(j0 + ROWS, n_keep);
   if (j0 >= n_keep) return;           // ragged lists: this unit has fewer chunks than the grid allows for
   const int32_t* idx = a.idx + (size_t)unit * a.idx_stride;
   const u32x4* src = a.src[tensor] + (PAGED ? (size_t)0 : (size_t)unit * a.n_cap * CPR);
@@ -106,10 +108,12 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
   // The control wavefront also looks at the chunk's indices themselves (two per lane, requested
   // here, judged after the searches below): strictly ascending, idx[j] >= j, inside the tensor.
   // A list that is not makes the in-place hazard analysis void; the status word records it.
-  int chk_cur[2] = {0, 0}, chk_prev[2] = {-1, -1};
+  int chk_cur[NCHK], chk_prev[NCHK];
+#pragma unroll
+  for (int t = 0; t < NCHK; ++t) { chk_cur[t] = 0; chk_prev[t] = -1; }
   if (control && tensor == 0) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < NCHK; ++t) {
       const int j = min(j0 + lane + 64 * t, j1 - 1);
       chk_cur[t] = idx[j];
       chk_prev[t] = j > 0 ? idx[j - 1] : -1;
@@ -140,14 +144,14 @@ __global__ __launch_bounds__(320) void k_compact(CompactArgs a) {
     if (a.inplace) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // rows are in registers
   } else if (a.inplace && !identity) {
     // earlier chunks c' whose sources [idx[first], idx[last]] meet my rows [j0, j1)
-    const int lo = first_true(c, lane, [&](int x) { return idx[x * kCompactRows + kCompactRows - 1] >= j0; });
-    const int hi = first_true(c, lane, [&](int x) { return idx[x * kCompactRows] >= j1; }) - 1;
+    const int lo = first_true(c, lane, [&](int x) { return idx[x * ROWS + ROWS - 1] >= j0; });
+    const int hi = first_true(c, lane, [&](int x) { return idx[x * ROWS] >= j1; }) - 1;
     if (lane == 0) { s_lo = lo; s_hi = hi; }
   }
   if (control && tensor == 0) {
     bool bad = false;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < NCHK; ++t) {
       const int j = min(j0 + lane + 64 * t, j1 - 1);
       bad |= chk_cur[t] <= chk_prev[t] || chk_cur[t] < j || chk_cur[t] >= a.n;
     }
@@ -310,11 +314,12 @@ hipError_t launch_compact(const Dims& d, const void* k, const void* v, int64_t n
   a.n_cap = n_cap;
   a.n_keep = (int)n_keep;
   a.units = d.units();
-  a.nch = (int)((n_keep + kCompactRows - 1) / kCompactRows);
+  const int rb = d.D * d.esize();
+  const int rows = rb == 128 ? compact_rows(128) : rb == 256 ? compact_rows(256) : rb == 512 ? compact_rows(512) : compact_rows(1024);
+  a.nch = (int)((n_keep + rows - 1) / rows);       // (never more chunks than the flag region was sized for)
   a.flags = flags;
   a.status = status;
   a.inplace = (k_out == k && v_out == v) ? 1 : 0;
-  const int rb = d.D * d.esize();
   const unsigned grid = 2u * a.units * a.nch;
 #define EA_COMPACT(RB)                                                \
   case RB:                                                             \
